@@ -1,0 +1,159 @@
+/*
+ * CPU oracle for the any-n weight-only GEMM.  TEST INFRASTRUCTURE ONLY.
+ *
+ * This file is the slow, plain definition the GPU library is checked against.
+ * Only the test-suite, the smoke check and the benchmark's cpu_baseline leg may
+ * call it; the product library never does and shares no code with it.
+ *
+ * What it computes (any4 paper):
+ *   - every weight is stored as an n-bit code that is a direct, unsigned index
+ *     into the 2^n-entry lookup table of ITS OWN ROW (section 2.4.1 "Arbitrary
+ *     Non-uniform Quantization: any4"; section 4.2 "tinygemm Library", last
+ *     paragraph: the codes are used as LUT indices);
+ *   - dequant(w_Q) = alpha * w_Q + beta (section 2.5.2 "Rounding"), with w_Q the
+ *     table entry, alpha/beta the scale/offset shared by a group of g = 128
+ *     consecutive weights along the reduction dimension (section 2.5.1,
+ *     "Groupwise", and the default g stated at the end of that section);
+ *   - y = x w^T with x: M x K, w: N x K (section 4.2, first paragraph), i.e.
+ *     y[m][n] = sum_k w[n][k] * x[m][k] (section 4.1, the per-element sum).
+ *
+ * Storage (fixed by the problem statement, not by the paper, whose own kernels
+ * use an undisclosed tile order): codes are packed along K into little-endian
+ * uint32 words, first code in the lowest bits; 4-bit: 8 per word, 2-bit: 16 per
+ * word, 3-bit: one contiguous bit stream per row (a code may straddle two words).
+ * Table, scale, offset and activations are bf16 bit patterns (uint16).
+ *
+ * Precision: the table value, scale and offset are widened to fp32 and combined
+ * with ONE fp32 rounding (fmaf); the contraction runs in fp64, sequentially in k.
+ *
+ * Pins (tests/test_oracle_*.py): exact rational brute force on tiny inputs, the
+ * int4 special case LUT = {-8..7}, code/LUT permutation invariance, shared-LUT
+ * (nf4-style) equivalence, closed forms (one-hot table, constant codes, zero
+ * table, unit-vector activations), reduction to a library fp64 matmul, pack /
+ * unpack round trips, and the bits-per-weight figure printed in section 2.4.1.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define ANY4O_GROUP 128
+
+static float bf16_bits_to_float(uint16_t b) {
+    uint32_t u = (uint32_t)b << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return f;
+}
+
+static int bits_ok(int bits) { return bits == 2 || bits == 3 || bits == 4; }
+
+/* number of uint32 words that hold one row of K codes */
+int64_t any4o_row_words(int64_t K, int bits) { return K * bits / 32; }
+
+/* code k of one packed row */
+uint32_t any4o_code(const uint32_t *row, int64_t k, int bits) {
+    int64_t b = k * bits;          /* bit position of the code inside the row */
+    int64_t word = b / 32;
+    int sh = (int)(b % 32);
+    uint64_t window = row[word];
+    if (sh + bits > 32)            /* only a 3-bit code can straddle two words */
+        window |= (uint64_t)row[word + 1] << 32;
+    return (uint32_t)((window >> sh) & ((1u << bits) - 1u));
+}
+
+/* one code per byte -> packed words.  Returns 0, or -1 on bad arguments,
+ * or -2 if some code does not fit in `bits` bits. */
+int any4o_pack(const uint8_t *codes_u8, int64_t N, int64_t K, int bits, uint32_t *packed) {
+    if (!codes_u8 || !packed || N < 1 || K < 1 || K % ANY4O_GROUP || !bits_ok(bits)) return -1;
+    int64_t W = any4o_row_words(K, bits);
+    memset(packed, 0, (size_t)(N * W) * sizeof(uint32_t));
+    for (int64_t n = 0; n < N; ++n) {
+        uint32_t *row = packed + n * W;
+        for (int64_t k = 0; k < K; ++k) {
+            uint32_t c = codes_u8[n * K + k];
+            if (c >> bits) return -2;
+            for (int i = 0; i < bits; ++i) {          /* bit by bit: no cleverness */
+                int64_t b = k * bits + i;
+                if ((c >> i) & 1u) row[b / 32] |= 1u << (b % 32);
+            }
+        }
+    }
+    return 0;
+}
+
+/* w[n][k] = fmaf(LUT[n][code(n,k)], scale[n][k/128], offset[n][k/128]) in fp32.
+ * Returns the number of elements for which (v*s)+o, rounded after each step,
+ * differs in bit pattern from the fused result (expected 0: a product of two bf16
+ * numbers is exact in fp32), or -1 on bad arguments. */
+int64_t any4o_dequant(const uint32_t *packed, const uint16_t *lut, const uint16_t *scale,
+                      const uint16_t *offset, int64_t N, int64_t K, int bits, float *w) {
+    if (!packed || !lut || !scale || !offset || !w || N < 1 || K < 1 || K % ANY4O_GROUP || !bits_ok(bits))
+        return -1;
+    int64_t W = any4o_row_words(K, bits), G = K / ANY4O_GROUP, L = 1 << bits;
+    int64_t differ = 0;
+    for (int64_t n = 0; n < N; ++n) {
+        for (int64_t k = 0; k < K; ++k) {
+            uint32_t c = any4o_code(packed + n * W, k, bits);
+            float v = bf16_bits_to_float(lut[n * L + c]);
+            float s = bf16_bits_to_float(scale[n * G + k / ANY4O_GROUP]);
+            float o = bf16_bits_to_float(offset[n * G + k / ANY4O_GROUP]);
+            float fused = fmaf(v, s, o);
+            volatile float prod = v * s;              /* force the intermediate rounding */
+            volatile float two_step = prod + o;
+            float ts = two_step;
+            if (memcmp(&fused, &ts, sizeof fused) != 0) ++differ;
+            w[n * K + k] = fused;
+        }
+    }
+    return differ;
+}
+
+/* y[m][n] = sum_{k=0..K-1} (double)w[n][k] * (double)x[m][k], k ascending, fp64.
+ * `threads` > 1 only distributes whole output rows n over OpenMP threads; the
+ * arithmetic of every output element is unchanged.  Returns 0 or -1. */
+int any4o_gemm(const uint16_t *x, const uint32_t *packed, const uint16_t *lut, const uint16_t *scale,
+               const uint16_t *offset, int64_t M, int64_t N, int64_t K, int bits, double *y, int threads) {
+    if (!x || !packed || !lut || !scale || !offset || !y || M < 1 || N < 1 || K < 1 ||
+        K % ANY4O_GROUP || !bits_ok(bits))
+        return -1;
+    int64_t W = any4o_row_words(K, bits), G = K / ANY4O_GROUP, L = 1 << bits;
+    if (threads < 1) threads = 1;
+#pragma omp parallel num_threads(threads)
+    {
+        float *wrow = (float *)malloc((size_t)K * sizeof(float));
+#pragma omp for schedule(static)
+        for (int64_t n = 0; n < N; ++n) {
+            for (int64_t k = 0; k < K; ++k) {
+                uint32_t c = any4o_code(packed + n * W, k, bits);
+                float v = bf16_bits_to_float(lut[n * L + c]);
+                float s = bf16_bits_to_float(scale[n * G + k / ANY4O_GROUP]);
+                float o = bf16_bits_to_float(offset[n * G + k / ANY4O_GROUP]);
+                wrow[k] = fmaf(v, s, o);
+            }
+            for (int64_t m = 0; m < M; ++m) {
+                double acc = 0.0;
+                for (int64_t k = 0; k < K; ++k)
+                    acc += (double)wrow[k] * (double)bf16_bits_to_float(x[m * K + k]);
+                y[m * N + n] = acc;
+            }
+        }
+        free(wrow);
+    }
+    return 0;
+}
+
+/* root mean square of n doubles */
+double any4o_rms(const double *y, int64_t n) {
+    double s = 0.0;
+    for (int64_t i = 0; i < n; ++i) s += y[i] * y[i];
+    return n > 0 ? sqrt(s / (double)n) : 0.0;
+}
+
+/* Bits of storage per weight for an N x K matrix: codes + per-row table +
+ * per-group scale and offset, all 16-bit metadata (section 2.4.1). */
+double any4o_bits_per_weight(int64_t K, int bits) {
+    double table = (double)(1 << bits) * 16.0 / (double)K;
+    double groups = (double)(K / ANY4O_GROUP) * 2.0 * 16.0 / (double)K;
+    return (double)bits + table + groups;
+}
