@@ -1,0 +1,259 @@
+#!/usr/bin/env python3
+"""Benchmark of the any4 GEMM hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--extras/--no-extras]
+
+A *step* is one pass of the hot path over one decoder layer of Llama-3-8B at M = 1: the four
+quantised linears (fused QKV, O, fused gate/up, down), i.e. four any4_gemm launches.  Successive
+steps use successive layers of a stack of `--layers` distinct synthetic layers (default 16, 1.9 GB
+of packed weights), so every launch streams its weights from HBM and not from the 256 MB
+last-level cache, exactly as token generation over a whole model does.  The K timed steps are
+replayed from one HIP graph (the launch sequence of a decode step is static), bracketed by
+synchronisation on both sides.
+
+The one JSON line printed at the end carries the contract fields plus
+  roofline      achieved GB/s of the decode kernel: algorithmic bytes per launch divided by
+                the average launch duration, measured with HIP events around every launch of
+                a second pass over the same steps (stream = torch's current stream, on which
+                the library is launched);
+  cpu_baseline  the CPU oracle timed on a bounded sample of the same workload;
+  extras        per-shape microseconds, other M, the 70B shapes and the M = 2048 matrix-core
+                path (context; not part of `value`).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0        # MI355X published HBM3E bandwidth
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def algorithmic_bytes(M, N, K, bits):
+    """Bytes the method must move per GEMM: packed codes + per-row tables + per-group scale and
+    offset + activations in + outputs out (dequantised weights are never counted)."""
+    return N * K * bits // 8 + N * (1 << bits) * 2 + 2 * N * (K // 128) * 2 + M * K * 2 + M * N * 2
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=640)
+    ap.add_argument("--warmup", type=int, default=64)
+    ap.add_argument("--layers", type=int, default=16)
+    ap.add_argument("--extras", dest="extras", action="store_true", default=True)
+    ap.add_argument("--no-extras", dest="extras", action="store_false")
+    ap.add_argument("--no-cpu-baseline", dest="cpu", action="store_false", default=True)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU only (--gpus 1); the path shards without "
+              "communication along N and with one small all-reduce along K, see DESIGN.md",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2507_04610_amd as any4
+    from paper_2507_04610_amd import inputs
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    any4.load_library()                      # raises if libany4.so was not built
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    bits = 4
+
+    def make_layer(shapes, M, seed):
+        layer = []
+        for i, (name, (N, K)) in enumerate(shapes.items()):
+            t = inputs.make_case_device(M, N, K, bits, seed=inputs.case_seed(seed, i), device=dev)
+            codes = any4.any4_pack(t["codes_u8"], bits)
+            ws_bytes = any4.any4_gemm_workspace_bytes(M, N, K, bits)
+            layer.append({
+                "name": name, "M": M, "N": N, "K": K, "x": t["x"], "codes": codes, "lut": t["lut"],
+                "scale": t["scale"], "offset": t["offset"],
+                "y": torch.empty((M, N), dtype=torch.bfloat16, device=dev),
+                "ws": torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev),
+                "bytes": algorithmic_bytes(M, N, K, bits),
+            })
+            del t["codes_u8"]
+        return layer
+
+    def launch(g):
+        any4.any4_gemm(g["x"], g["codes"], g["lut"], g["scale"], g["offset"], bits, out=g["y"], workspace=g["ws"])
+
+    # ------------------------------------------------------------------ headline workload
+    M = 1
+    layers = [make_layer(inputs.LLAMA3_8B_SHAPES, M, seed=100 + l) for l in range(args.layers)]
+    torch.cuda.synchronize()
+    step_bytes = sum(g["bytes"] for g in layers[0])
+
+    def run_steps(first, count):
+        for s in range(first, first + count):
+            for g in layers[s % args.layers]:
+                launch(g)
+
+    run_steps(0, args.warmup)                                   # untimed warm-up, eager
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run_steps(0, args.steps)
+    graph.replay()                                              # untimed: first replay uploads the graph
+    torch.cuda.synchronize()
+
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0.record()
+    graph.replay()                                              # EXACTLY --steps steps
+    e1.record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    wall_ms = (t1 - t0) * 1e3
+    ms_per_step = wall_ms / args.steps
+    value = step_bytes / (ms_per_step * 1e-3) / 1e9             # GB/s, whole job
+
+    # per-launch durations: same steps, eager, one event pair around every launch
+    n_launch = args.steps * len(layers[0])
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_launch)]
+    i = 0
+    for s in range(args.steps):
+        for g in layers[s % args.layers]:
+            evs[i][0].record()
+            launch(g)
+            evs[i][1].record()
+            i += 1
+    torch.cuda.synchronize()
+    per_shape_us = {g["name"]: [] for g in layers[0]}
+    i = 0
+    total_kernel_ms = 0.0
+    for s in range(args.steps):
+        for g in layers[s % args.layers]:
+            dt = evs[i][0].elapsed_time(evs[i][1])
+            per_shape_us[g["name"]].append(dt * 1e3)
+            total_kernel_ms += dt
+            i += 1
+    avg_launch_us = total_kernel_ms * 1e3 / n_launch
+    bytes_per_launch = step_bytes / len(layers[0])
+    achieved = bytes_per_launch / (avg_launch_us * 1e-6) / 1e9
+
+    extras = {
+        "graph_event_ms_per_step": e0.elapsed_time(e1) / args.steps,
+        "llama3_8b_M1_us": {k: float(np.median(v)) for k, v in per_shape_us.items()},
+        "llama3_8b_M1_GBps": {g["name"]: g["bytes"] / (float(np.median(per_shape_us[g["name"]])) * 1e-6) / 1e9
+                              for g in layers[0]},
+    }
+
+    # ------------------------------------------------------------------ context measurements
+    def time_gemm(g, reps, rotate=None):
+        """median microseconds of one launch (event pair per launch); rotate = list of
+        equivalent problems to cycle through so weights come from HBM."""
+        probs = rotate or [g]
+        for p in probs[:2]:
+            launch(p)
+        torch.cuda.synchronize()
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for r in range(reps):
+            ev[r][0].record()
+            launch(probs[r % len(probs)])
+            ev[r][1].record()
+        torch.cuda.synchronize()
+        return float(np.median([a.elapsed_time(b) * 1e3 for a, b in ev]))
+
+    if args.extras:
+        del graph
+        m8 = {}
+        for gi, g in enumerate(layers[0]):
+            rot = []
+            for l in range(args.layers):
+                p = dict(layers[l][gi])
+                p["M"] = 8
+                p["x"] = torch.randn((8, p["K"]), device=dev).to(torch.bfloat16)
+                p["y"] = torch.empty((8, p["N"]), dtype=torch.bfloat16, device=dev)
+                p["ws"] = torch.empty(max(any4.any4_gemm_workspace_bytes(8, p["N"], p["K"], bits), 16),
+                                      dtype=torch.uint8, device=dev)
+                rot.append(p)
+            us = time_gemm(rot[0], 64, rot)
+            m8[g["name"]] = {"us": us, "GBps": algorithmic_bytes(8, g["N"], g["K"], bits) / (us * 1e-6) / 1e9}
+        extras["llama3_8b_M8"] = m8
+        # prefill, M = 2048, on the 8B shapes (weights of layer 0)
+        pf = {}
+        for g in layers[0]:
+            p = dict(g)
+            p["M"] = 2048
+            p["x"] = torch.randn((2048, p["K"]), device=dev).to(torch.bfloat16)
+            p["y"] = torch.empty((2048, p["N"]), dtype=torch.bfloat16, device=dev)
+            p["ws"] = torch.empty(max(any4.any4_gemm_workspace_bytes(2048, p["N"], p["K"], bits), 16),
+                                  dtype=torch.uint8, device=dev)
+            us = time_gemm(p, 5)
+            tf = 2.0 * 2048 * p["N"] * p["K"] / (us * 1e-6) / 1e12
+            pf[g["name"]] = {"us": us, "TFLOPs": tf, "frac_of_bf16_peak": tf / MFMA_BF16_PEAK_TFLOPS}
+            del p
+        extras["llama3_8b_M2048"] = pf
+        layers_keep = layers[0]
+        del layers
+        torch.cuda.empty_cache()
+        # 70B shapes, M = 1 and 16, rotating over enough copies to exceed the last-level cache
+        big = {}
+        for i, (name, (N, K)) in enumerate(inputs.LLAMA3_70B_SHAPES.items()):
+            copies = max(2, min(8, int(1.2e9 // (N * K // 2)) + 1))
+            for Mx in (1, 16):
+                rot = [make_layer({name: (N, K)}, Mx, seed=300 + c)[0] for c in range(copies)]
+                us = time_gemm(rot[0], 24, rot)
+                by = algorithmic_bytes(Mx, N, K, bits)
+                big[f"{name}_M{Mx}"] = {"us": us, "GBps": by / (us * 1e-6) / 1e9,
+                                        "frac_of_hbm_peak": by / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS}
+                del rot
+                torch.cuda.empty_cache()
+        extras["llama3_70b"] = big
+        layers = [layers_keep]
+
+    # ------------------------------------------------------------------ CPU oracle beside it
+    cpu = None
+    if args.cpu:
+        from oracle import any4_oracle as oracle
+        threads = min(16, os.cpu_count() or 1)
+        # bounded sample: the first `rows` output rows of each of the four linears of one layer
+        cases = []
+        for i, (name, (N, K)) in enumerate(inputs.LLAMA3_8B_SHAPES.items()):
+            rows = max(threads, N // 8)
+            cs = inputs.make_case(1, rows, K, bits, seed=inputs.case_seed(100, i))
+            cases.append((cs, oracle.pack(cs.codes_u8, bits)))
+        t0 = time.perf_counter()
+        reps = 0
+        while time.perf_counter() - t0 < 10.0:
+            for cs, packed in cases:
+                oracle.gemm(cs.x, packed, cs.lut, cs.scale, cs.offset, cs.K, bits, threads=threads)
+            reps += 1
+        dt = (time.perf_counter() - t0) / reps
+        sample_bytes = sum(algorithmic_bytes(1, cs.N, cs.K, bits) for cs, _ in cases)
+        cpu = {"value": sample_bytes / dt / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
+               "sample": f"first N/8 output rows of each of the four Llama-3-8B linears at M=1 "
+                         f"({sample_bytes / 1e6:.1f} MB algorithmic), {reps} passes, {dt * 1e3:.1f} ms per pass"}
+
+    out = {
+        "metric": "any4 GEMM achieved HBM GB/s (M=1) on Llama-3-8B shapes",
+        "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 x any4 -> fp32 accumulate -> bf16", "data": "synthetic",
+        "config": {"workload": "Llama-3-8B decode linears (qkv 6144x4096, o 4096x4096, gate_up 28672x4096, "
+                               "down 4096x14336), any4 g=128, M=1; step = the four GEMMs of one layer, "
+                               f"rotating over {args.layers} distinct layers, HIP-graph replay",
+                   "M": 1, "bits": bits, "group": 128, "bytes_per_step": step_bytes},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                     "kernel": "decode GEMM (any4, M=1)", "avg_launch_us": avg_launch_us,
+                     "bytes_per_launch": bytes_per_launch},
+        "cpu_baseline": cpu,
+        "extras": extras,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,107 @@
+/*
+ * any4.h - C ABI of libany4: the inference hot path of any4 (learned per-row 4-bit
+ * numeric format; also 3- and 2-bit "anyn") on AMD MI355X (gfx950).
+ *
+ * The operation (any4 paper, section 4.2 "tinygemm Library", first paragraph):
+ *     y = x w^T,   x: M x K activations,   w: N x K quantised weights,   y: M x N
+ * where every weight is stored as an n-bit code that indexes the 2^n-entry lookup
+ * table of its own output row (section 2.4.1) and is dequantised with the scale and
+ * offset of its group of 128 consecutive weights along K (section 2.5.1 "Groupwise",
+ * section 2.5.2: dequant(w_Q) = alpha * w_Q + beta):
+ *     w[n][k] = LUT[n][code[n][k]] * scale[n][k/128] + offset[n][k/128].
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers owned by the caller.  The library never
+ *     allocates, frees or keeps them.  All matrices are dense, row-major, no strides.
+ *   - bf16 values travel as uint16_t bit patterns.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the default
+ *     stream) and the call returns without waiting for it.
+ *   - Return value: ANY4_OK (0) or a negative error code.  On error nothing was
+ *     launched and no output byte was written.  No exception or abort crosses the ABI.
+ *   - K must be a positive multiple of 128 (the group size); M, N >= 1; bits is 4, 3
+ *     or 2.  Every pointer must be 16-byte aligned.
+ *   - The library holds no mutable global state; calls on different streams may run
+ *     concurrently as long as their outputs and workspaces do not overlap.
+ *
+ * Packed code layout (codes[N][K*bits/32], uint32 words, per row, along K):
+ *   bits = 4:  8 codes per word, code k in bits [4(k%8), 4(k%8)+4) of word k/8
+ *   bits = 2: 16 codes per word, code k in bits [2(k%16), 2(k%16)+2) of word k/16
+ *   bits = 3:  one contiguous little-endian bit stream per row: code k occupies bits
+ *              [3k, 3k+3) of the row, counted from bit 0 of word 0 (a code may straddle
+ *              two words); a row is 3K/32 words.
+ */
+#ifndef ANY4_H
+#define ANY4_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ANY4_OK             0
+#define ANY4_ERR_NULL      -1   /* a required pointer is NULL */
+#define ANY4_ERR_SHAPE     -2   /* M, N or K < 1, or K not a multiple of 128 */
+#define ANY4_ERR_BITS      -3   /* bits is not 4, 3 or 2 */
+#define ANY4_ERR_ALIGN     -4   /* a pointer is not 16-byte aligned */
+#define ANY4_ERR_WORKSPACE -5   /* workspace smaller than any4_gemm_workspace_bytes() */
+#define ANY4_ERR_HIP       -6   /* the HIP runtime refused a launch */
+
+#define ANY4_GROUP 128          /* weights per scale/offset group along K */
+
+/*
+ * any4_pack - offline packing of codes (one per byte) into the layout above.
+ * The paper pre-arranges weights offline as well (section 4.2, second paragraph);
+ * its tile order is specific to its hardware, the layout here is the plain row-major one.
+ *   codes_u8  in   uint8 [N][K], each value < 2^bits (higher bits are masked off)
+ *   codes     out  uint32 [N][K*bits/32], fully overwritten
+ */
+int any4_pack(const uint8_t* codes_u8, int64_t N, int64_t K, int bits,
+              uint32_t* codes, void* stream);
+
+/*
+ * any4_dequant - materialise the dequantised weights (sections 2.4.1 and 2.5.2):
+ *     w[n][k] = fma(LUT[n][code], scale[n][k/128], offset[n][k/128])
+ * evaluated in fp32 with a single rounding; the result is defined bit for bit.
+ *   codes   in   uint32 [N][K*bits/32]
+ *   lut     in   bf16   [N][2^bits]   the row's table; entry order carries no meaning
+ *   scale   in   bf16   [N][K/128]
+ *   offset  in   bf16   [N][K/128]
+ *   w       out  fp32   [N][K], fully overwritten
+ */
+int any4_dequant(const uint32_t* codes, const uint16_t* lut, const uint16_t* scale,
+                 const uint16_t* offset, int64_t N, int64_t K, int bits,
+                 float* w, void* stream);
+
+/*
+ * any4_gemm - y[m][n] = sum_k x[m][k] * w[n][k] with w as defined above, never
+ * materialised (section 4.2: weights are dequantised on the fly inside the GEMM).
+ * Products are accumulated in fp32 (order unspecified but fixed for given shapes: the
+ * result is reproducible run to run); y is rounded to bf16, round-to-nearest-even.
+ * Small M (<= 16, token generation) takes a memory-bound kernel, larger M a
+ * matrix-core kernel; the choice depends only on (M, N, K, bits).
+ *   x          in   bf16 [M][K]
+ *   y          out  bf16 [M][N], fully overwritten
+ *   workspace  scratch of at least any4_gemm_workspace_bytes(M, N, K, bits) bytes,
+ *              16-byte aligned; may be NULL when that size is 0.  Contents on entry
+ *              are ignored, contents on exit are unspecified.
+ */
+int any4_gemm(const uint16_t* x, const uint32_t* codes, const uint16_t* lut,
+              const uint16_t* scale, const uint16_t* offset,
+              int64_t M, int64_t N, int64_t K, int bits,
+              uint16_t* y, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Bytes of workspace any4_gemm needs for this problem (0 for invalid arguments). */
+size_t any4_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int bits);
+
+/* Static, human-readable text for a return code. */
+const char* any4_strerror(int code);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int any4_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ANY4_H */

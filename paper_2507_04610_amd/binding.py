@@ -1,0 +1,141 @@
+"""Thin Python binding of libany4's C ABI (include/any4.h).
+
+Argument marshalling only: every function takes torch tensors that already live in device
+memory, checks dtype / shape / contiguity, and passes raw pointers plus the current HIP stream
+to the library.  No arithmetic of the method happens here, and there is no fallback: if the
+shared library is missing or a call is made with host tensors, this module raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libany4.so")
+GROUP = 128
+
+EXPORTS = ("any4_pack", "any4_dequant", "any4_gemm", "any4_gemm_workspace_bytes",
+           "any4_strerror", "any4_version")
+
+
+class Any4Error(RuntimeError):
+    pass
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libany4.so from the package directory (build it with
+    `python -m paper_2507_04610_amd.build`); raises if it is not there."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise Any4Error(f"{LIB_PATH} is missing: run `python -m paper_2507_04610_amd.build` first")
+    lib = ctypes.CDLL(LIB_PATH)
+    i64, vp, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
+    lib.any4_pack.restype = ci
+    lib.any4_pack.argtypes = [vp, i64, i64, ci, vp, vp]
+    lib.any4_dequant.restype = ci
+    lib.any4_dequant.argtypes = [vp, vp, vp, vp, i64, i64, ci, vp, vp]
+    lib.any4_gemm.restype = ci
+    lib.any4_gemm.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, ci, vp, vp, ctypes.c_size_t, vp]
+    lib.any4_gemm_workspace_bytes.restype = ctypes.c_size_t
+    lib.any4_gemm_workspace_bytes.argtypes = [i64, i64, i64, ci]
+    lib.any4_strerror.restype = ctypes.c_char_p
+    lib.any4_strerror.argtypes = [ci]
+    lib.any4_version.restype = ci
+    lib.any4_version.argtypes = []
+    _lib = lib
+    return lib
+
+
+def _check(rc: int, what: str) -> None:
+    if rc != 0:
+        raise Any4Error(f"{what} failed: {load_library().any4_strerror(rc).decode()} ({rc})")
+
+
+def _dev(t: torch.Tensor, dtype, name: str) -> int:
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise Any4Error(f"{name} must be a tensor in device memory")
+    if t.dtype != dtype:
+        raise Any4Error(f"{name} must have dtype {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise Any4Error(f"{name} must be contiguous")
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def row_words(K: int, bits: int) -> int:
+    return K * bits // 32
+
+
+def any4_version() -> int:
+    return int(load_library().any4_version())
+
+
+def any4_strerror(code: int) -> str:
+    return load_library().any4_strerror(code).decode()
+
+
+def any4_gemm_workspace_bytes(M: int, N: int, K: int, bits: int = 4) -> int:
+    return int(load_library().any4_gemm_workspace_bytes(M, N, K, bits))
+
+
+def any4_pack(codes_u8: torch.Tensor, bits: int = 4, out: torch.Tensor | None = None) -> torch.Tensor:
+    """uint8 [N,K] codes (one per byte) -> packed words, int32 tensor [N, K*bits/32]
+    (torch has no usable uint32; the bit patterns are what matters)."""
+    lib = load_library()
+    N, K = codes_u8.shape
+    src = _dev(codes_u8, torch.uint8, "codes_u8")
+    if out is None:
+        out = torch.empty((N, max(K * bits // 32, 0)), dtype=torch.int32, device=codes_u8.device)
+    dst = _dev(out, torch.int32, "out")
+    _check(lib.any4_pack(src, N, K, bits, dst, _stream()), "any4_pack")
+    return out
+
+
+def any4_dequant(codes: torch.Tensor, lut: torch.Tensor, scale: torch.Tensor, offset: torch.Tensor,
+                 K: int, bits: int = 4, out: torch.Tensor | None = None) -> torch.Tensor:
+    """fp32 [N,K] dequantised weights."""
+    lib = load_library()
+    N = codes.shape[0]
+    pc = _dev(codes, torch.int32, "codes")
+    pl = _dev(lut, torch.bfloat16, "lut")
+    ps = _dev(scale, torch.bfloat16, "scale")
+    po = _dev(offset, torch.bfloat16, "offset")
+    if out is None:
+        out = torch.empty((N, K), dtype=torch.float32, device=codes.device)
+    pw = _dev(out, torch.float32, "out")
+    _check(lib.any4_dequant(pc, pl, ps, po, N, K, bits, pw, _stream()), "any4_dequant")
+    return out
+
+
+def any4_gemm(x: torch.Tensor, codes: torch.Tensor, lut: torch.Tensor, scale: torch.Tensor,
+              offset: torch.Tensor, bits: int = 4, out: torch.Tensor | None = None,
+              workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """bf16 [M,N] = x[M,K] . dequant(codes, lut, scale, offset)[N,K]^T."""
+    lib = load_library()
+    M, K = x.shape
+    N = codes.shape[0]
+    px = _dev(x, torch.bfloat16, "x")
+    pc = _dev(codes, torch.int32, "codes")
+    pl = _dev(lut, torch.bfloat16, "lut")
+    ps = _dev(scale, torch.bfloat16, "scale")
+    po = _dev(offset, torch.bfloat16, "offset")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.bfloat16, device=x.device)
+    py = _dev(out, torch.bfloat16, "out")
+    need = int(lib.any4_gemm_workspace_bytes(M, N, K, bits))
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    pw = workspace.data_ptr() if workspace is not None else None
+    wbytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib.any4_gemm(px, pc, pl, ps, po, M, N, K, bits, py, pw, wbytes, _stream()), "any4_gemm")
+    return out

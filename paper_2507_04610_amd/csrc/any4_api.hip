@@ -1,0 +1,99 @@
+// C ABI of libany4 (see include/any4.h): argument validation, kernel selection, launches.
+#include "any4.h"
+#include "any4_internal.h"
+
+namespace any4 {
+
+static bool bits_ok(int bits) { return bits == 4 || bits == 3 || bits == 2; }
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+static int shape_check(int64_t N, int64_t K, int bits) {
+    if (!bits_ok(bits)) return ANY4_ERR_BITS;
+    if (N < 1 || K < 1 || K % ANY4_GROUP != 0) return ANY4_ERR_SHAPE;
+    return ANY4_OK;
+}
+
+constexpr int kDecodeMaxM = 16;
+
+GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int bits) {
+    GemmPlan p{};
+    p.decode = M <= kDecodeMaxM;
+    p.ksplit = 1;
+    if (p.decode) {
+        // one wavefront per (row, K slice): aim for at least ~8K wavefronts in flight, but keep
+        // every slice at least one full 64-lane step long
+        const int unit_codes = bits == 4 ? 32 : (bits == 2 ? 64 : 128);
+        const int64_t steps = (K / unit_codes + 63) / 64;
+        int64_t want = (8192 + N - 1) / N;
+        if (want > steps) want = steps;
+        if (want > 64) want = 64;
+        if (want < 1) want = 1;
+        p.ksplit = (int)want;
+    }
+    if (p.decode) p.workspace = p.ksplit > 1 ? (size_t)p.ksplit * (size_t)M * (size_t)N * sizeof(float) : 0;
+    else p.workspace = prefill_workspace_bytes(M, K);
+    return p;
+}
+
+}  // namespace any4
+
+using namespace any4;
+
+extern "C" {
+
+int any4_pack(const uint8_t* codes_u8, int64_t N, int64_t K, int bits, uint32_t* codes, void* stream) {
+    if (!codes_u8 || !codes) return ANY4_ERR_NULL;
+    if (int rc = shape_check(N, K, bits)) return rc;
+    if (!aligned16(codes_u8) || !aligned16(codes)) return ANY4_ERR_ALIGN;
+    return launch_pack(codes_u8, N, K, bits, codes, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? ANY4_OK : ANY4_ERR_HIP;
+}
+
+int any4_dequant(const uint32_t* codes, const uint16_t* lut, const uint16_t* scale,
+                 const uint16_t* offset, int64_t N, int64_t K, int bits, float* w, void* stream) {
+    if (!codes || !lut || !scale || !offset || !w) return ANY4_ERR_NULL;
+    if (int rc = shape_check(N, K, bits)) return rc;
+    if (!aligned16(codes) || !aligned16(lut) || !aligned16(scale) || !aligned16(offset) || !aligned16(w))
+        return ANY4_ERR_ALIGN;
+    return launch_dequant(codes, lut, scale, offset, N, K, bits, w, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? ANY4_OK : ANY4_ERR_HIP;
+}
+
+size_t any4_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int bits) {
+    if (M < 1 || shape_check(N, K, bits) != ANY4_OK) return 0;
+    return plan_gemm(M, N, K, bits).workspace;
+}
+
+int any4_gemm(const uint16_t* x, const uint32_t* codes, const uint16_t* lut, const uint16_t* scale,
+              const uint16_t* offset, int64_t M, int64_t N, int64_t K, int bits, uint16_t* y,
+              void* workspace, size_t workspace_bytes, void* stream) {
+    if (!x || !codes || !lut || !scale || !offset || !y) return ANY4_ERR_NULL;
+    if (int rc = shape_check(N, K, bits)) return rc;
+    if (M < 1) return ANY4_ERR_SHAPE;
+    if (!aligned16(x) || !aligned16(codes) || !aligned16(lut) || !aligned16(scale) ||
+        !aligned16(offset) || !aligned16(y) || !aligned16(workspace))
+        return ANY4_ERR_ALIGN;
+    const GemmPlan plan = plan_gemm(M, N, K, bits);
+    if (plan.workspace > 0 && (!workspace || workspace_bytes < plan.workspace)) return ANY4_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e = plan.decode
+        ? launch_decode(x, codes, lut, scale, offset, M, N, K, bits, plan, y, static_cast<float*>(workspace), s)
+        : launch_prefill(x, codes, lut, scale, offset, M, N, K, bits, y, workspace, s);
+    return e == hipSuccess ? ANY4_OK : ANY4_ERR_HIP;
+}
+
+const char* any4_strerror(int code) {
+    switch (code) {
+        case ANY4_OK: return "ok";
+        case ANY4_ERR_NULL: return "a required pointer is NULL";
+        case ANY4_ERR_SHAPE: return "bad shape: M, N, K must be >= 1 and K a multiple of 128";
+        case ANY4_ERR_BITS: return "bits must be 4, 3 or 2";
+        case ANY4_ERR_ALIGN: return "a pointer is not 16-byte aligned";
+        case ANY4_ERR_WORKSPACE: return "workspace is missing or smaller than any4_gemm_workspace_bytes()";
+        case ANY4_ERR_HIP: return "the HIP runtime refused a kernel launch";
+        default: return "unknown any4 error code";
+    }
+}
+
+int any4_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,42 @@
+// Device-side helpers shared by the HIP kernels of libany4 (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace any4 {
+
+constexpr int kGroup = 128;   // weights per scale/offset group along K
+constexpr int kWave = 64;     // CDNA wavefront
+
+__device__ __forceinline__ float bf16_to_f32(uint32_t bits16) {
+    return __uint_as_float(bits16 << 16);
+}
+// high / low half of a packed bf16 pair, widened to fp32
+__device__ __forceinline__ float bf16lo_to_f32(uint32_t pair) { return __uint_as_float(pair << 16); }
+__device__ __forceinline__ float bf16hi_to_f32(uint32_t pair) { return __uint_as_float(pair & 0xFFFF0000u); }
+
+// fp32 -> bf16, round-to-nearest-even; NaN stays a quiet NaN
+__device__ __forceinline__ uint32_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x40u;
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+
+// words per packed row
+__host__ __device__ __forceinline__ int64_t row_words(int64_t K, int bits) { return K * bits / 32; }
+
+// Sum over the 64 lanes of a wavefront; every lane gets the total.
+// Row-level steps use DPP row rotations, the cross-row steps ds_swizzle / readlane.
+__device__ __forceinline__ float wave_sum(float v) {
+    // within rows of 16 lanes
+    v += __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(v), 0x121 /*row_ror:1*/, 0xF, 0xF, false));
+    v += __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(v), 0x122 /*row_ror:2*/, 0xF, 0xF, false));
+    v += __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(v), 0x124 /*row_ror:4*/, 0xF, 0xF, false));
+    v += __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(v), 0x128 /*row_ror:8*/, 0xF, 0xF, false));
+    // across the four rows: swap with lane^16 (ds_swizzle), then lane^32
+    v += __uint_as_float(__builtin_amdgcn_ds_swizzle(__float_as_uint(v), 0x401F /*bit-mode xor 0x10*/));
+    v += __uint_as_float(__builtin_amdgcn_ds_bpermute(((int)(threadIdx.x & 63) ^ 32) << 2, __float_as_uint(v)));
+    return v;
+}
+
+}  // namespace any4

@@ -1,0 +1,37 @@
+// Host-side declarations shared between the C ABI (any4_api.hip) and the kernel files.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace any4 {
+
+// How any4_gemm runs a given problem; a pure function of (M, N, K, bits) so that
+// any4_gemm_workspace_bytes() and any4_gemm() always agree.
+struct GemmPlan {
+    bool decode;          // true: memory-bound small-M kernel, false: matrix-core kernel
+    int ksplit;           // number of K slices whose fp32 partials are reduced in a 2nd pass
+    size_t workspace;     // bytes of scratch: K-slice partials (decode) or group sums of x (matrix-core path)
+};
+GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int bits);
+
+hipError_t launch_pack(const uint8_t* codes_u8, int64_t N, int64_t K, int bits,
+                       uint32_t* codes, hipStream_t stream);
+hipError_t launch_dequant(const uint32_t* codes, const uint16_t* lut, const uint16_t* scale,
+                          const uint16_t* offset, int64_t N, int64_t K, int bits,
+                          float* w, hipStream_t stream);
+hipError_t launch_decode(const uint16_t* x, const uint32_t* codes, const uint16_t* lut,
+                         const uint16_t* scale, const uint16_t* offset,
+                         int64_t M, int64_t N, int64_t K, int bits, const GemmPlan& plan,
+                         uint16_t* y, float* partial, hipStream_t stream);
+hipError_t launch_prefill(const uint16_t* x, const uint32_t* codes, const uint16_t* lut,
+                          const uint16_t* scale, const uint16_t* offset,
+                          int64_t M, int64_t N, int64_t K, int bits,
+                          uint16_t* y, void* workspace, hipStream_t stream);
+
+// Matrix-core path: padded length of the "group" dimension (two bf16 columns per group of 128,
+// rounded up to the MFMA K granularity of 16) and the scratch it needs for the group sums of x.
+inline int prefill_kp(int64_t K) { return (int)((2 * (K / 128) + 15) / 16 * 16); }
+size_t prefill_workspace_bytes(int64_t M, int64_t K);
+
+}  // namespace any4

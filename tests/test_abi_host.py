@@ -1,0 +1,86 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, and rejects bad arguments before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "any4.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2507_04610_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2507_04610_amd import build
+        build.build_library(verbose=False)
+    return binding.load_library()
+
+
+def declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(any4_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_symbols()
+    assert {"any4_pack", "any4_dequant", "any4_gemm", "any4_gemm_workspace_bytes",
+            "any4_strerror", "any4_version"} <= set(names)
+    for name in names:
+        assert hasattr(lib, name), name
+
+
+def test_binding_lists_the_same_entry_points():
+    from paper_2507_04610_amd import binding
+    assert sorted(binding.EXPORTS) == declared_symbols()
+
+
+def test_version_and_error_strings(lib):
+    assert lib.any4_version() >= 100
+    seen = set()
+    for code in range(0, -7, -1):
+        s = lib.any4_strerror(code).decode()
+        assert s and s not in seen
+        seen.add(s)
+    assert b"unknown" in lib.any4_strerror(-99)
+
+
+def test_bad_arguments_are_rejected_before_any_launch(lib):
+    A = 0x1000          # fake, 16-byte aligned, never dereferenced: validation fails first
+    # NULL pointers
+    assert lib.any4_pack(None, 4, 128, 4, A, None) == -1
+    assert lib.any4_dequant(A, None, A, A, 4, 128, 4, A, None) == -1
+    assert lib.any4_gemm(A, A, A, A, A, 1, 4, 128, 4, None, None, 0, None) == -1
+    # shapes
+    assert lib.any4_pack(A, 0, 128, 4, A, None) == -2
+    assert lib.any4_pack(A, 4, 100, 4, A, None) == -2
+    assert lib.any4_dequant(A, A, A, A, 4, 0, 4, A, None) == -2
+    assert lib.any4_gemm(A, A, A, A, A, 0, 4, 128, 4, A, None, 0, None) == -2
+    assert lib.any4_gemm(A, A, A, A, A, 1, 4, 192, 4, A, None, 0, None) == -2
+    # bits
+    for bits in (0, 1, 5, 8, -4):
+        assert lib.any4_pack(A, 4, 128, bits, A, None) == -3
+        assert lib.any4_gemm(A, A, A, A, A, 1, 4, 128, bits, A, None, 0, None) == -3
+    # alignment
+    assert lib.any4_pack(A + 4, 4, 128, 4, A, None) == -4
+    assert lib.any4_dequant(A, A + 2, A, A, 4, 128, 4, A, None) == -4
+    assert lib.any4_gemm(A, A, A, A, A, 1, 4, 128, 4, A + 8, None, 0, None) == -4
+
+
+def test_workspace_contract(lib):
+    # invalid problems need no workspace
+    assert lib.any4_gemm_workspace_bytes(1, 4, 100, 4) == 0
+    assert lib.any4_gemm_workspace_bytes(0, 4, 128, 4) == 0
+    assert lib.any4_gemm_workspace_bytes(1, 4, 128, 7) == 0
+    # a short row-count with a long K is split along K and needs fp32 partials: a multiple of M*N*4
+    M, N, K = 4, 64, 16384
+    need = lib.any4_gemm_workspace_bytes(M, N, K, 4)
+    assert need > 0 and need % (M * N * 4) == 0
+    A = 0x1000
+    assert lib.any4_gemm(A, A, A, A, A, M, N, K, 4, A, None, 0, None) == -5
+    assert lib.any4_gemm(A, A, A, A, A, M, N, K, 4, A, A, need - 1, None) == -5
+    # the matrix-core path keeps per-group sums of x: far smaller than x itself
+    assert 0 < lib.any4_gemm_workspace_bytes(2048, 4096, 4096, 4) <= 2048 * 4096 * 2 // 32

@@ -1,0 +1,218 @@
+"""Parity of the HIP path against the CPU oracle, through the C ABI, on a real MI355X.
+
+Bars: packed words and dequantised fp32 weights bit-exact; GEMM outputs within
+1e-2 * rms(y_fp64) + 2^-8 * |y_fp64| (half a bf16 ulp of output rounding) elementwise.
+Small shapes are compared element by element; the full benchmark shapes on sampled output
+rows (all M columns of each sampled row), with rms taken over the sampled block.
+"""
+import numpy as np
+import pytest
+
+from paper_2507_04610_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def any4():
+    if not torch.cuda.is_available():
+        pytest.fail("no GPU visible: the parity tests must run on the GPU box")
+    import paper_2507_04610_amd as lib
+    lib.load_library()                      # raises if libany4.so is missing
+    return lib
+
+
+def dev_bf16(a_u16):
+    return torch.from_numpy(np.ascontiguousarray(a_u16).view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def dev_codes(packed_u32):
+    return torch.from_numpy(np.ascontiguousarray(packed_u32).view(np.int32)).cuda()
+
+
+def host_u32(t):
+    return t.cpu().numpy().view(np.uint32)
+
+
+def host_bf16_as_f64(t):
+    return inputs.bf16_bits_to_f32(t.view(torch.int16).cpu().numpy().view(np.uint16)).astype(np.float64)
+
+
+def check_gemm(y_dev, y64, rms, what):
+    y = host_bf16_as_f64(y_dev)
+    tol = 1e-2 * rms + np.abs(y64) * 2.0 ** -8
+    err = np.abs(y - y64)
+    worst = np.unravel_index(np.argmax(err - tol), err.shape)
+    assert np.all(err <= tol), (what, "worst", worst, float(err[worst]), float(tol[worst]), "rms", rms)
+    return float((err / (1e-2 * rms)).max())
+
+
+# ------------------------------------------------------------------------------ pack
+@pytest.mark.parametrize("bits", (4, 3, 2))
+@pytest.mark.parametrize("N,K", [(1, 128), (5, 384), (257, 1152), (64, 4096)])
+def test_pack_bit_exact(any4, oracle, bits, N, K):
+    rng = np.random.default_rng(100 + bits + N)
+    codes = rng.integers(0, 1 << bits, size=(N, K), dtype=np.uint8)
+    got = host_u32(any4.any4_pack(torch.from_numpy(codes).cuda(), bits))
+    assert np.array_equal(got, oracle.pack(codes, bits))
+
+
+def test_pack_masks_high_bits(any4, oracle):
+    rng = np.random.default_rng(5)
+    codes = rng.integers(0, 256, size=(3, 256), dtype=np.uint8)
+    for bits in (4, 3, 2):
+        got = host_u32(any4.any4_pack(torch.from_numpy(codes).cuda(), bits))
+        assert np.array_equal(got, oracle.pack(codes & ((1 << bits) - 1), bits))
+
+
+# ------------------------------------------------------------------------------ dequant
+@pytest.mark.parametrize("bits", (4, 3, 2))
+@pytest.mark.parametrize("N,K", [(1, 128), (3, 384), (130, 640), (257, 4224), (16, 14336)])
+def test_dequant_bit_exact(any4, oracle, bits, N, K):
+    cs = inputs.make_case(1, N, K, bits, seed=inputs.case_seed(2, N % 7, bits))
+    packed = oracle.pack(cs.codes_u8, bits)
+    w_ref = oracle.dequant(packed, cs.lut, cs.scale, cs.offset, K, bits)
+    w = any4.any4_dequant(dev_codes(packed), dev_bf16(cs.lut), dev_bf16(cs.scale), dev_bf16(cs.offset), K, bits)
+    assert np.array_equal(w.cpu().numpy().view(np.uint32), w_ref.view(np.uint32))
+
+
+def test_dequant_special_values(any4, oracle):
+    """Unsorted table with +-0, sub-normal, tiny and huge entries; zero offsets in half the rows."""
+    N, K, bits = 8, 512, 4
+    cs = inputs.make_case(1, N, K, bits, seed=9)
+    specials = np.array([0x0000, 0x8000, 0x0001, 0x8001, 0x007F, 0x0080, 0x7F7F, 0xFF7F,
+                         0x3F80, 0xBF80, 0x0100, 0x4000, 0x3400, 0xB400, 0x2000, 0x5000], np.uint16)
+    lut = np.stack([np.roll(specials, n) for n in range(N)])
+    offset = cs.offset.copy()
+    offset[::2] = 0
+    packed = oracle.pack(cs.codes_u8, bits)
+    w_ref = oracle.dequant(packed, lut, cs.scale, offset, K, bits)
+    w = any4.any4_dequant(dev_codes(packed), dev_bf16(lut), dev_bf16(cs.scale), dev_bf16(offset), K, bits)
+    assert np.array_equal(w.cpu().numpy().view(np.uint32), w_ref.view(np.uint32))
+
+
+# ------------------------------------------------------------------------------ gemm, element by element
+def run_gemm_case(any4, oracle, M, N, K, bits, seed, mutate=None):
+    cs = inputs.make_case(M, N, K, bits, seed)
+    if mutate:
+        mutate(cs)
+    packed = oracle.pack(cs.codes_u8, bits)
+    y64 = oracle.gemm(cs.x, packed, cs.lut, cs.scale, cs.offset, K, bits, threads=8)
+    codes_dev = any4.any4_pack(torch.from_numpy(cs.codes_u8).cuda(), bits)
+    assert np.array_equal(host_u32(codes_dev), packed)
+    y = any4.any4_gemm(dev_bf16(cs.x), codes_dev, dev_bf16(cs.lut), dev_bf16(cs.scale), dev_bf16(cs.offset), bits)
+    torch.cuda.synchronize()
+    assert y.shape == (M, N) and y.dtype == torch.bfloat16
+    return check_gemm(y, y64, oracle.rms(y64), (M, N, K, bits))
+
+
+def test_gemm_config1(any4, oracle):
+    """M=1, N=256, K=512, seed 0."""
+    run_gemm_case(any4, oracle, 1, 256, 512, 4, seed=0)
+
+
+@pytest.mark.parametrize("bits", (4, 3, 2))
+@pytest.mark.parametrize("M", (1, 2, 3, 5, 8, 13, 16))
+def test_gemm_decode_small(any4, oracle, bits, M):
+    # ragged N (not a multiple of any tile), K spanning several steps with a short tail
+    run_gemm_case(any4, oracle, M, 333, 4224, bits, seed=inputs.case_seed(3, bits, M))
+
+
+@pytest.mark.parametrize("bits", (4, 3, 2))
+@pytest.mark.parametrize("M,N,K", [(1, 1, 128), (4, 7, 128), (16, 64, 16384), (2, 40, 28672), (1, 2049, 256)])
+def test_gemm_decode_edges(any4, oracle, bits, M, N, K):
+    run_gemm_case(any4, oracle, M, N, K, bits, seed=inputs.case_seed(4, bits, M))
+
+
+@pytest.mark.parametrize("bits", (4, 3, 2))
+@pytest.mark.parametrize("M,N,K", [(17, 128, 128), (100, 200, 256), (256, 384, 1024), (129, 130, 640), (300, 64, 2048)])
+def test_gemm_prefill_small(any4, oracle, bits, M, N, K):
+    run_gemm_case(any4, oracle, M, N, K, bits, seed=inputs.case_seed(5, bits, M % 10))
+
+
+def test_gemm_zero_offset_and_unsorted_table(any4, oracle):
+    def mutate(cs):
+        cs.offset[:] = 0                                   # symmetric scaling: beta = 0
+        rng = np.random.default_rng(1)
+        for n in range(cs.N):
+            cs.lut[n] = cs.lut[n][rng.permutation(cs.lut.shape[1])]
+    for M in (1, 16, 64):
+        run_gemm_case(any4, oracle, M, 192, 1024, 4, seed=77, mutate=mutate)
+
+
+def test_gemm_is_reproducible(any4, oracle):
+    cs = inputs.make_case(4, 64, 16384, 4, seed=12)
+    codes = any4.any4_pack(torch.from_numpy(cs.codes_u8).cuda(), 4)
+    args = (dev_bf16(cs.x), codes, dev_bf16(cs.lut), dev_bf16(cs.scale), dev_bf16(cs.offset), 4)
+    assert any4.any4_gemm_workspace_bytes(4, 64, 16384, 4) > 0     # the split-K route
+    a = any4.any4_gemm(*args).view(torch.int16).cpu()
+    for _ in range(3):
+        assert torch.equal(a, any4.any4_gemm(*args).view(torch.int16).cpu())
+
+
+def test_gemm_rejects_small_workspace_and_leaves_output_alone(any4):
+    cs = inputs.make_case(4, 64, 16384, 4, seed=12)
+    codes = any4.any4_pack(torch.from_numpy(cs.codes_u8).cuda(), 4)
+    y = torch.full((4, 64), 7.0, dtype=torch.bfloat16, device="cuda")
+    ws = torch.empty(16, dtype=torch.uint8, device="cuda")
+    with pytest.raises(any4.Any4Error):
+        any4.any4_gemm(dev_bf16(cs.x), codes, dev_bf16(cs.lut), dev_bf16(cs.scale), dev_bf16(cs.offset), 4,
+                       out=y, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.all(y == 7.0)
+
+
+# ------------------------------------------------------------------------------ full benchmark shapes, sampled rows
+SAMPLE_ROWS = 48
+
+
+def sampled_rows_check(any4, oracle, shape_name, N, K, bits, Ms, seed):
+    Mmax = max(Ms)
+    cs = inputs.make_case(Mmax, N, K, bits, seed)
+    codes_dev = any4.any4_pack(torch.from_numpy(cs.codes_u8).cuda(), bits)
+    lut, scale, offset = dev_bf16(cs.lut), dev_bf16(cs.scale), dev_bf16(cs.offset)
+    rng = np.random.default_rng(seed + 1)
+    rows = np.unique(np.concatenate([[0, 1, N - 2, N - 1], rng.integers(0, N, SAMPLE_ROWS)]))
+    packed_rows = oracle.pack(cs.codes_u8[rows], bits)
+    assert np.array_equal(host_u32(codes_dev[torch.from_numpy(rows).cuda()]), packed_rows)
+    # dequant of the sampled rows, bit-exact, through a call on the whole matrix slice by slice
+    w_ref = oracle.dequant(packed_rows, cs.lut[rows], cs.scale[rows], cs.offset[rows], K, bits)
+    idx = torch.from_numpy(rows).cuda()
+    w = any4.any4_dequant(codes_dev[idx].contiguous(), lut[idx].contiguous(), scale[idx].contiguous(),
+                          offset[idx].contiguous(), K, bits)
+    assert np.array_equal(w.cpu().numpy().view(np.uint32), w_ref.view(np.uint32))
+    worst = 0.0
+    for M in Ms:
+        x = cs.x[:M]
+        y64 = oracle.gemm(x, packed_rows, cs.lut[rows], cs.scale[rows], cs.offset[rows], K, bits, threads=8)
+        y = any4.any4_gemm(dev_bf16(x), codes_dev, lut, scale, offset, bits)
+        torch.cuda.synchronize()
+        worst = max(worst, check_gemm(y[:, idx], y64, oracle.rms(y64), (shape_name, M, N, K, bits)))
+    return worst
+
+
+@pytest.mark.parametrize("name", list(inputs.LLAMA3_8B_SHAPES))
+def test_llama3_8b_decode_and_prefill_shapes(any4, oracle, name):
+    """Configs 2 and 4: M = 1, 8 (decode) and M = 2048 (prefill) on the 8B linears."""
+    N, K = inputs.LLAMA3_8B_SHAPES[name]
+    i = list(inputs.LLAMA3_8B_SHAPES).index(name)
+    sampled_rows_check(any4, oracle, name, N, K, 4, (1, 8, 2048), seed=inputs.case_seed(20, i))
+
+
+@pytest.mark.parametrize("name", list(inputs.LLAMA3_70B_SHAPES))
+def test_llama3_70b_batch_sweep(any4, oracle, name):
+    """Config 3: M in {1, 2, 4, 8, 16} on the 70B linears."""
+    N, K = inputs.LLAMA3_70B_SHAPES[name]
+    i = list(inputs.LLAMA3_70B_SHAPES).index(name)
+    sampled_rows_check(any4, oracle, name, N, K, 4, (1, 2, 4, 8, 16), seed=inputs.case_seed(30, i))
+
+
+@pytest.mark.parametrize("bits", (3, 2))
+@pytest.mark.parametrize("name", list(inputs.LLAMA3_70B_SHAPES))
+def test_llama3_70b_any3_any2(any4, oracle, name, bits):
+    """Config 5: 3- and 2-bit variants at M = 1 and 16 on the 70B linears."""
+    N, K = inputs.LLAMA3_70B_SHAPES[name]
+    i = list(inputs.LLAMA3_70B_SHAPES).index(name)
+    sampled_rows_check(any4, oracle, name, N, K, bits, (1, 16), seed=inputs.case_seed(50 + bits, i))
