@@ -1,6 +1,10 @@
 // C ABI of libany4 (see include/any4.h): argument validation, kernel selection, launches.
 #include "any4.h"
 #include "any4_internal.h"
+#include "any4_splitk.h"
+#include <atomic>
+#include <chrono>
+#include <stdlib.h>
 
 namespace any4 {
 
@@ -14,11 +18,41 @@ static int shape_check(int64_t N, int64_t K, int bits) {
 
 constexpr int kDecodeMaxM = 16;
 
+// Per-call tag for the split-K arrival counters (see any4_splitk.h): 56 bits, never zero, distinct
+// from call to call and, through the clock-derived start value, from earlier processes' left-overs.
+static unsigned long long next_epoch() {
+    static std::atomic<unsigned long long> counter{
+        (unsigned long long)std::chrono::steady_clock::now().time_since_epoch().count() * 0x9E3779B97F4A7C15ull};
+    unsigned long long e = counter.fetch_add(1, std::memory_order_relaxed) & 0x00FFFFFFFFFFFFFFull;
+    return e ? e : 1;
+}
+
 GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int bits) {
     GemmPlan p{};
     p.decode = M <= kDecodeMaxM;
+    p.tile = p.decode && bits == 4;
+    p.m1 = p.tile && M == 1 && (K / ANY4_GROUP) % 8 == 0;
     p.ksplit = 1;
-    if (p.decode) {
+    p.gslice = 0;
+    const int64_t G = K / ANY4_GROUP;
+    if (p.tile) {
+        // blocks of 64 rows x one K slice of `gslice` groups.  Long slices amortise the per-block
+        // table build, so K is split only as far as needed to have about one block per compute
+        // unit; a slice is a multiple of 8 groups (one 2-group chunk per wavefront of a 4-wave
+        // block, and 16-byte aligned scale rows) and never longer than the kernels' LDS budget.
+        const int64_t tiles = (N + 63) / 64;
+        const int64_t want_slices = (256 + tiles - 1) / tiles;
+        int64_t gs = (G + want_slices - 1) / want_slices;
+        gs = (gs + 7) / 8 * 8;
+        const int64_t limit = p.m1 ? decode_m1_gslice_limit() : decode_tile_gslice_limit((int)M);
+        if (gs > limit) gs = limit;
+        if ((G + gs - 1) / gs > kMaxSplit) gs = ((G + kMaxSplit - 1) / kMaxSplit + 7) / 8 * 8;
+#ifdef ANY4_TUNING
+        if (const char* e = getenv("ANY4_TUNE_GSLICE")) gs = atoi(e);
+#endif
+        p.gslice = (int)gs;
+        p.ksplit = (int)((G + gs - 1) / gs);
+    } else if (p.decode) {
         // one wavefront per (row, K slice): aim for at least ~8K wavefronts in flight, but keep
         // every slice at least one full 64-lane step long
         const int unit_codes = bits == 4 ? 32 : (bits == 2 ? 64 : 128);
@@ -29,7 +63,9 @@ GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int bits) {
         if (want < 1) want = 1;
         p.ksplit = (int)want;
     }
-    if (p.decode) p.workspace = p.ksplit > 1 ? (size_t)p.ksplit * (size_t)M * (size_t)N * sizeof(float) : 0;
+    if (p.tile)
+        p.workspace = p.ksplit > 1 ? splitk_counter_bytes((N + 63) / 64) + (size_t)p.ksplit * (size_t)M * (size_t)N * sizeof(float) : 0;
+    else if (p.decode) p.workspace = p.ksplit > 1 ? (size_t)p.ksplit * (size_t)M * (size_t)N * sizeof(float) : 0;
     else p.workspace = prefill_workspace_bytes(M, K);
     return p;
 }
@@ -75,9 +111,17 @@ int any4_gemm(const uint16_t* x, const uint32_t* codes, const uint16_t* lut, con
     const GemmPlan plan = plan_gemm(M, N, K, bits);
     if (plan.workspace > 0 && (!workspace || workspace_bytes < plan.workspace)) return ANY4_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    hipError_t e = plan.decode
-        ? launch_decode(x, codes, lut, scale, offset, M, N, K, bits, plan, y, static_cast<float*>(workspace), s)
-        : launch_prefill(x, codes, lut, scale, offset, M, N, K, bits, y, workspace, s);
+    hipError_t e;
+    if (plan.tile) {
+        const unsigned long long epoch = next_epoch();
+        e = plan.m1
+            ? launch_decode_m1(x, codes, lut, scale, offset, N, K, plan, y, workspace, epoch, s)
+            : launch_decode_tile(x, codes, lut, scale, offset, M, N, K, plan, y, workspace, epoch, s);
+    } else if (plan.decode) {
+        e = launch_decode(x, codes, lut, scale, offset, M, N, K, bits, plan, y, static_cast<float*>(workspace), s);
+    } else {
+        e = launch_prefill(x, codes, lut, scale, offset, M, N, K, bits, y, workspace, s);
+    }
     return e == hipSuccess ? ANY4_OK : ANY4_ERR_HIP;
 }
 

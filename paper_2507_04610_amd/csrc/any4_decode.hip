@@ -118,6 +118,12 @@ __global__ __launch_bounds__(256) void reduce_slices_kernel(const float* __restr
     y[i] = (uint16_t)f32_to_bf16(s);
 }
 
+hipError_t launch_reduce_slices(const float* partial, int ksplit, int64_t MN, uint16_t* y, hipStream_t stream) {
+    hipLaunchKernelGGL(reduce_slices_kernel, dim3((unsigned)((MN + 255) / 256)), dim3(256), 0, stream,
+                       partial, ksplit, MN, y);
+    return hipGetLastError();
+}
+
 template <int BITS>
 static hipError_t launch_decode_bits(const uint16_t* x, const uint32_t* codes, const uint16_t* lut,
                                      const uint16_t* scale, const uint16_t* offset, int M, int64_t N,
