@@ -17,6 +17,19 @@ static int shape_check(int64_t N, int64_t K, int bits) {
 }
 
 constexpr int kDecodeMaxM = 16;
+constexpr int kStreamMaxM = 32;
+
+// Compute units of the current device (256 on MI355X); only shapes the work split, never results.
+int device_compute_units() {
+    static const int cus = [] {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
+            n = 256;
+        return n;
+    }();
+    return cus;
+}
 
 // Per-call tag for the split-K arrival counters (see any4_splitk.h): 56 bits, never zero, distinct
 // from call to call and, through the clock-derived start value, from earlier processes' left-overs.
@@ -29,6 +42,15 @@ static unsigned long long next_epoch() {
 
 GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int bits) {
     GemmPlan p{};
+    if (bits == 4 && M <= kStreamMaxM && N <= ((int64_t)1 << 35)) {
+        p.sp = plan_stream(M, N, K, device_compute_units());
+        if (p.sp.gw > 0) {
+            p.decode = p.stream = true;
+            p.ksplit = p.sp.slabs;
+            p.workspace = p.sp.workspace;
+            return p;
+        }
+    }
     p.decode = M <= kDecodeMaxM;
     p.tile = p.decode && bits == 4;
     p.m1 = p.tile && M == 1 && (K / ANY4_GROUP) % 8 == 0;
@@ -112,7 +134,9 @@ int any4_gemm(const uint16_t* x, const uint32_t* codes, const uint16_t* lut, con
     if (plan.workspace > 0 && (!workspace || workspace_bytes < plan.workspace)) return ANY4_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t e;
-    if (plan.tile) {
+    if (plan.stream) {
+        e = launch_decode_stream(x, codes, lut, scale, offset, M, N, K, plan.sp, y, workspace, next_epoch(), s);
+    } else if (plan.tile) {
         const unsigned long long epoch = next_epoch();
         e = plan.m1
             ? launch_decode_m1(x, codes, lut, scale, offset, N, K, plan, y, workspace, epoch, s)

@@ -1,0 +1,651 @@
+// Memory-bound any4 GEMM for small M (token generation, 1 <= M <= 16): persistent streaming kernel.
+//
+// y[m][n] = sum_k x[m][k] * (LUT[n][code[n][k]] * scale[n][k/128] + offset[n][k/128])
+// (any4 paper, section 4.2 for y = x w^T with on-the-fly dequantisation, sections 2.4.1 and
+// 2.5.2 for the per-row table and alpha * w_Q + beta).
+//
+// Lookup.  The paper keeps the 16-entry table in a register and looks codes up with a warp
+// shuffle; it rejects a shared-memory table of all 16 x 16 value PAIRS (one lookup per packed
+// byte) because of bank conflicts (section 4.2, last paragraph).  On CDNA4 the pair table is
+// conflict free by construction.  A block works on 16 weight rows at a time; lane l of every
+// wavefront works on row n = l % 16 and on quarter q = l / 16 of each group of 128 codes.  Entry
+// e of row n is stored twice, at LDS bytes e * 256 + n * 8 and + 4 (and + 128 for the second of
+// two table buffers); lane (n, q) reads copy q % 2, so the 32 lanes LDS serves together hit 32
+// different banks.  One v_perm_b32 forms a lookup address (byte j of a code word -> address
+// byte 1; buffer, row and copy -> byte 0); the lookup returns two bf16 table values, already
+// packed as a matrix-core operand.
+//
+// Contraction.  v_mfma_f32_16x16x32_bf16 multiplies 16 rows x 32 codes by the activations
+// (A operand: one row per m, rows >= M are zero).  Matrix-core throughput exceeds what the
+// streamed codes need by a wide margin for every M <= 16, so the kernel costs nearly the same
+// for M = 1 and M = 16: the time is that of reading the codes once.
+//
+// Scale and offset never touch individual weights.  With X[m][g] the sum of the 128
+// activations of group g,
+//     y[m][n] = sum_g ( scale[n][g] * P[m][n][g] + offset[n][g] * X[m][g] ),
+//     P[m][n][g] = sum_{k in g} x[m][k] * LUT[n][code[n][k]]      (exact bf16 x bf16 products)
+// P comes out of 4 MFMAs per group and is folded in with one fma per accumulator; the offset
+// term of all groups of a wavefront is one more MFMA whose A operand is X split into a bf16
+// high and low part (16 significant bits) and whose B operand is the offsets themselves.
+//
+// Work split ("K-stationary").  The K axis is cut into slabs of at most WAVES * GW groups.  A
+// block belongs to one slab; wavefront w owns GW consecutive groups of it and keeps the
+// activations of those groups in registers, as ready-made A operands, for its whole life.  The
+// block then walks over its share of the 16-row tiles.  For every tile each wavefront streams
+// the 64 * GW bytes per row that belong to its groups (the four lanes of a row read four
+// consecutive 16-byte pieces), looks the codes up, multiplies, and leaves its partial sums in
+// LDS; after one barrier per tile the partial sums of every output are added in a fixed order
+// and stored.  The table of tile t+1 is built while tile t is being processed (two table
+// buffers), and the code registers of a tile are refilled for tile t + kDepth as soon as their
+// lookup addresses have been formed.  Loads in the steady state are unconditional (past the
+// end of the block's share they re-read its last tile, which is cached), which lets the
+// compiler count outstanding loads exactly.
+//
+// Small per-tile inputs (the rows' tables, scales and offsets: 2.5 KB per tile against 4 KB of
+// codes per wavefront) are not read by every wavefront: for tile t one wavefront, taking turns,
+// loads them four tiles ahead with five instructions and passes them on through LDS (AUX mode;
+// it needs K/128 to be a multiple of 4 for the 8-byte alignment of its loads, otherwise every
+// wavefront reads what it needs itself).
+//
+// With more than one slab the partial sums go to the workspace and the block that is last to
+// finish a tile adds the slabs in slab order: results do not depend on the order in which
+// blocks run.
+#include "any4_device.h"
+#include "any4_internal.h"
+#include "any4_splitk.h"
+#include <stdlib.h>
+#include <type_traits>
+
+namespace any4 {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+namespace stream {
+
+constexpr int kTile = 16;                              // weight rows per tile
+#ifndef ANY4_STREAM_DEPTH
+#define ANY4_STREAM_DEPTH 2
+#endif
+constexpr int kDepth = ANY4_STREAM_DEPTH;              // tiles of code loads in flight per wavefront (2 or 4)
+constexpr int kTableBytes = 256 * 256;                 // 256 entries x (2 buffers x 16 rows x 2 copies x 4 B)
+constexpr int kListTiles = 1024;                       // tiles whose slabs a block combines per round
+constexpr int kAuxDist = 4;                            // tiles between the load of a tile's small inputs and their use
+constexpr int kAuxRow = 72;                            // LDS bytes per row of scales (64 + 8 of padding against bank conflicts)
+constexpr int kAuxScale = 0, kAuxOffset = kTile * kAuxRow, kAuxLut = 2 * kTile * kAuxRow;
+constexpr int kAuxSlot = kAuxLut + kTile * 32;         // 2816 B: scales, offsets and tables of one tile
+constexpr int red_bytes(int waves) { return 2 * waves * 4 * 64 * 4; }     // [2][waves][4][64] fp32 partial sums
+constexpr int aux_base(int waves) { return kTableBytes + red_bytes(waves); }
+constexpr int list_base(int waves) { return aux_base(waves) + kAuxDist * kAuxSlot; }
+constexpr int lds_bytes(int waves) { return list_base(waves) + (1 + kListTiles) * 4; }
+
+#ifdef ANY4_STAMPS
+// timing probes for tuning builds: time stamps at the natural LDS synchronisation points of a tile
+// step, collected in LDS and written out when the block ends
+__device__ long long* g_any4_dbg_stream = nullptr;
+constexpr int kStampSteps = 32;
+#define ST_STAMP(i) do { if (lane == 0 && (t - t0) < kStampSteps) stamps[((w * kStampSteps) + (t - t0)) * 4 + (i)] = wall_clock64(); } while (0)
+#else
+#define ST_STAMP(i) do {} while (0)
+#endif
+
+struct Params {
+    const uint16_t* x;
+    const uint32_t* codes;
+    const uint16_t* lut;
+    const uint16_t* scale;
+    const uint16_t* offset;
+    uint16_t* y;
+    float* partial;                  // [slabs][M][N] fp32, slabs > 1 only
+    unsigned long long* counters;    // [tiles], slabs > 1 only
+    unsigned long long epoch;
+    int64_t N, K;
+    int M, G;                        // G = K / 128
+    int slabs, slab_groups;          // groups per slab (the last slab may have fewer)
+    int blocks_per_slab, tiles;
+};
+
+// LDS barrier that does not wait for outstanding global loads (the prefetched codes stay in flight)
+__device__ __forceinline__ void lds_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+__device__ __forceinline__ float sum8(const uint4& v) {
+    return ((bf16lo_to_f32(v.x) + bf16hi_to_f32(v.x)) + (bf16lo_to_f32(v.y) + bf16hi_to_f32(v.y))) +
+           ((bf16lo_to_f32(v.z) + bf16hi_to_f32(v.z)) + (bf16lo_to_f32(v.w) + bf16hi_to_f32(v.w)));
+}
+
+// One arrival at a tile's counter by a single thread; true if this was the last of `ksplit`.
+// The caller has made its partial sums visible (stores issued and waited for) beforehand.
+__device__ __forceinline__ bool arrive_one(unsigned long long* c, int ksplit, unsigned long long epoch) {
+    unsigned long long old = __hip_atomic_load(c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    unsigned long long cnt;
+    for (;;) {
+        cnt = ((old >> 8) == epoch) ? (old & 0xFFull) + 1ull : 1ull;
+        const unsigned long long nv = (epoch << 8) | cnt;
+        if (__hip_atomic_compare_exchange_strong(c, &old, nv, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                                                 __HIP_MEMORY_SCOPE_AGENT))
+            break;
+    }
+    const bool last = cnt == (unsigned long long)ksplit;
+    if (last) __hip_atomic_store(c, epoch << 8, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return last;
+}
+
+// WAVES   wavefronts per block: 8 (two per SIMD, up to 256 registers each) or 16 (four per SIMD)
+// GW      groups (of 128 weights) a wavefront owns: 1, 2 or 4
+// AUX     tables, scales and offsets of a tile are loaded by one wavefront and shared through LDS;
+//         requires K/128 and the slab size to be multiples of 4 (8-byte aligned loads)
+template <int WAVES, int GW, bool AUX>
+__global__ __launch_bounds__(WAVES * 64, 1) void decode_stream_kernel(const Params p) {
+    static_assert(WAVES == 8 || WAVES == 16, "the table build is written for 8 or 16 wavefronts");
+    static_assert(kDepth == 4 || kDepth == 2, "the tile loop is unrolled by kDepth");
+    constexpr int kThreads = WAVES * 64;
+    constexpr int NP = (GW + 1) / 2;                     // packed bf16 pairs holding GW scales
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    float* red = reinterpret_cast<float*>(smem + kTableBytes);          // [2][WAVES][4][64]
+    unsigned char* const aux = smem + aux_base(WAVES);                  // [kAuxDist] slots
+    int* lastlist = reinterpret_cast<int*>(smem + list_base(WAVES));    // [0] = count
+#ifdef ANY4_STAMPS
+    long long* stamps = reinterpret_cast<long long*>(smem + lds_bytes(WAVES));
+    for (int i = threadIdx.x; i < WAVES * kStampSteps * 4; i += WAVES * 64) stamps[i] = 0;
+#endif
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n = lane & 15, q = lane >> 4;
+
+    const int slab = blockIdx.x / p.blocks_per_slab, bb = blockIdx.x - slab * p.blocks_per_slab;
+    if (slab >= p.slabs) return;
+    const int t0 = (int)((int64_t)bb * p.tiles / p.blocks_per_slab);
+    const int t1 = (int)((int64_t)(bb + 1) * p.tiles / p.blocks_per_slab);
+    if (t0 >= t1) return;
+    const int ntiles = t1 - t0;
+
+    const int M = p.M, G = p.G;
+    const int64_t N = p.N, K = p.K;
+    const int gs0 = slab * p.slab_groups;
+    const int sg = min(p.slab_groups, G - gs0);          // groups of this slab
+    const int ngw = max(0, min(GW, sg - w * GW));        // groups this wavefront really has (wave-uniform)
+    // first group of this wavefront; a wavefront without groups points at the slab's first group and
+    // keeps zero activations, scales and offsets, so whatever it reads contributes nothing
+    const int gw0 = ngw > 0 ? gs0 + w * GW : gs0;
+    auto group_of = [&](int gi) -> int { return gw0 + min(gi, max(ngw, 1) - 1); };        // clamped, wave-uniform
+
+    // Addresses are a wave-uniform base (tile, group) plus a 32-bit per-lane byte offset (row, quarter),
+    // so that the loads take their base from scalar registers.  In the problem's last tile the rows
+    // past N are clamped to row N - 1 (they are read, never stored); only the lane offsets differ.
+    const int last_tile = p.tiles - 1;
+    const int nc = min(n, (int)(N - 1 - (int64_t)last_tile * kTile));        // this lane's row inside the last tile
+    const uint32_t row_bytes = (uint32_t)(K / 2);
+    const uint32_t vc_norm = (uint32_t)n * row_bytes + (uint32_t)q * 16u, vc_last = (uint32_t)nc * row_bytes + (uint32_t)q * 16u;
+    const uint32_t vl_norm = (uint32_t)n * 32u, vl_last = (uint32_t)nc * 32u;
+    const uint32_t vs_norm = (uint32_t)n * (uint32_t)G * 2u, vs_last = (uint32_t)nc * (uint32_t)G * 2u;
+    const char* const codes_b = reinterpret_cast<const char*>(p.codes);
+    const char* const lut_b = reinterpret_cast<const char*>(p.lut);
+    const char* const scale_b = reinterpret_cast<const char*>(p.scale);
+    const char* const offset_b = reinterpret_cast<const char*>(p.offset);
+
+    // ---- codes: a ring of kDepth register sets indexed by (tile - t0) % kDepth
+    uint4 cw[kDepth][GW];
+    auto codes_ptr = [&](int t, int gi) -> const uint4* {
+        const char* base = codes_b + (int64_t)t * (kTile * (int64_t)row_bytes) + group_of(gi) * 64;
+        return reinterpret_cast<const uint4*>(base + (t == last_tile ? vc_last : vc_norm));
+    };
+
+    // ---- table source of a tile.  The 256 entries of a row are written by its 4 * WAVES threads:
+    //   8 wavefronts: thread (w, n, q) writes high nibble 2w + q/2, low nibbles 8 (q % 2) .. + 8
+    //  16 wavefronts: thread (w, n, q) writes high nibble w,        low nibbles 4 q .. + 4
+    // so it needs that part of the row's table and the dword that holds LUT[hi].
+    using LutLo = std::conditional_t<WAVES == 8, uint4, uint2>;
+    const uint32_t lut_lo_off = WAVES == 8 ? (uint32_t)(q & 1) * 16u : (uint32_t)q * 8u;
+    const uint32_t lut_hi_off = WAVES == 8 ? (uint32_t)w * 4u : (uint32_t)(w >> 1) * 4u;
+    auto load_lut = [&](LutLo& lo, uint32_t& hi, int t) {          // straight from memory
+        const char* base = lut_b + (int64_t)t * (kTile * 32);
+        const uint32_t v = t == last_tile ? vl_last : vl_norm;
+        lo = *reinterpret_cast<const LutLo*>(base + (v + lut_lo_off));
+        hi = *reinterpret_cast<const uint32_t*>(base + lut_hi_off + v);
+    };
+    // table of a tile into buffer `par`: entry e of row n at dword e * 64 + par * 32 + n * 2, both copies
+    const int hi_nib = WAVES == 8 ? 2 * w + (q >> 1) : w, lo_nib0 = WAVES == 8 ? 8 * (q & 1) : 4 * q;
+    uint32_t* const tdst = reinterpret_cast<uint32_t*>(smem) + (hi_nib * 16 + lo_nib0) * 64 + n * 2;
+    auto build_table = [&](const LutLo& lo, uint32_t hi, int par) {
+        uint32_t hv;
+        if constexpr (WAVES == 8) hv = (q & 2) ? (hi & 0xFFFF0000u) : (hi << 16);
+        else hv = (w & 1) ? (hi & 0xFFFF0000u) : (hi << 16);
+        uint32_t* dst = tdst + par * 32;
+        constexpr int NE = WAVES == 8 ? 8 : 4;
+        uint32_t L[NE / 2];
+        if constexpr (WAVES == 8) { L[0] = lo.x; L[1] = lo.y; L[2] = lo.z; L[3] = lo.w; }
+        else { L[0] = lo.x; L[1] = lo.y; }
+#pragma unroll
+        for (int i = 0; i < NE; ++i) {
+            const uint32_t lv = (i & 1) ? (L[i >> 1] >> 16) : (L[i >> 1] & 0xFFFFu);
+            *reinterpret_cast<uint2*>(dst + i * 64) = make_uint2(lv | hv, lv | hv);
+        }
+    };
+
+    // ---- AUX mode: the tile's scales, offsets and tables, loaded by one wavefront into registers
+    //      (lane (n, j): scale / offset groups 4j .. 4j+3 and 16 + 4j .. 16 + 4j+3 of the slab; lanes
+    //      with j < 2: half j of the row's table) and written to an LDS slot two tiles later
+    uint2 axs[2], axo[2];
+    uint4 axl;
+    auto aux_load = [&](int t) {
+        const int64_t tile_off = (int64_t)t * (kTile * 2) * G + gs0 * 2;
+        const uint32_t vs = (t == last_tile ? vs_last : vs_norm) + (uint32_t)q * 8u;
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+            if ((c * 4 + q) * 4 < sg) {
+                axs[c] = *reinterpret_cast<const uint2*>(scale_b + tile_off + c * 32 + vs);
+                axo[c] = *reinterpret_cast<const uint2*>(offset_b + tile_off + c * 32 + vs);
+            }
+        if (q < 2)
+            axl = *reinterpret_cast<const uint4*>(lut_b + (int64_t)t * (kTile * 32) + ((t == last_tile ? vl_last : vl_norm) + (uint32_t)q * 16u));
+    };
+    auto aux_write = [&](int slot) {
+        unsigned char* s = aux + slot * kAuxSlot;
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+            if ((c * 4 + q) * 4 < sg) {
+                *reinterpret_cast<uint2*>(s + kAuxScale + n * kAuxRow + (c * 4 + q) * 8) = axs[c];
+                *reinterpret_cast<uint2*>(s + kAuxOffset + n * kAuxRow + (c * 4 + q) * 8) = axo[c];
+            }
+        if (q < 2) *reinterpret_cast<uint4*>(s + kAuxLut + n * 32 + q * 16) = axl;
+    };
+    auto aux_read_lut = [&](LutLo& lo, uint32_t& hi, int slot) {
+        const unsigned char* s = aux + slot * kAuxSlot + kAuxLut + n * 32;
+        lo = *reinterpret_cast<const LutLo*>(s + lut_lo_off);
+        hi = *reinterpret_cast<const uint32_t*>(s + lut_hi_off);
+    };
+
+    // ---- scales and offsets of the wavefront's groups for one tile, as packed bf16 pairs
+    //      (group gi in half gi % 2 of word gi / 2)
+    auto aux_read_so = [&](uint32_t (&sp)[NP], uint32_t (&op)[NP], int slot) {
+        const unsigned char* s = aux + slot * kAuxSlot + n * kAuxRow + (w * GW) * 2;
+        if constexpr (GW == 4) {
+            const uint2 a = *reinterpret_cast<const uint2*>(s + kAuxScale), b = *reinterpret_cast<const uint2*>(s + kAuxOffset);
+            sp[0] = a.x; sp[1] = a.y; op[0] = b.x; op[1] = b.y;
+        } else if constexpr (GW == 2) {
+            sp[0] = *reinterpret_cast<const uint32_t*>(s + kAuxScale);
+            op[0] = *reinterpret_cast<const uint32_t*>(s + kAuxOffset);
+        } else {
+            sp[0] = *reinterpret_cast<const uint16_t*>(s + kAuxScale);
+            op[0] = *reinterpret_cast<const uint16_t*>(s + kAuxOffset);
+        }
+        if (ngw == 0) {                                  // nothing was written for a wavefront without groups
+#pragma unroll
+            for (int i = 0; i < NP; ++i) { sp[i] = 0; op[i] = 0; }
+        }
+    };
+    // without AUX: every wavefront reads its own scales, offsets (one bf16 per load) and table rows,
+    // in rings like the codes
+    uint32_t sraw[kDepth][GW], oraw[kDepth][GW];
+    LutLo lut_lo[kDepth];
+    uint32_t lut_hi[kDepth];
+    auto load_so = [&](uint32_t (&sr)[GW], uint32_t (&orw)[GW], int t) {
+        const int64_t tile_off = (int64_t)t * (kTile * 2) * G;
+        const uint32_t v = t == last_tile ? vs_last : vs_norm;
+#pragma unroll
+        for (int gi = 0; gi < GW; ++gi) {
+            sr[gi] = *reinterpret_cast<const uint16_t*>(scale_b + tile_off + group_of(gi) * 2 + v);
+            orw[gi] = *reinterpret_cast<const uint16_t*>(offset_b + tile_off + group_of(gi) * 2 + v);
+        }
+    };
+    auto pack_so = [&](uint32_t (&sp)[NP], uint32_t (&op)[NP], const uint32_t (&sr)[GW], const uint32_t (&orw)[GW]) {
+#pragma unroll
+        for (int i = 0; i < NP; ++i) { sp[i] = 0; op[i] = 0; }
+#pragma unroll
+        for (int gi = 0; gi < GW; ++gi)
+            if (gi < ngw) { sp[gi >> 1] |= sr[gi] << (16 * (gi & 1)); op[gi >> 1] |= orw[gi] << (16 * (gi & 1)); }
+    };
+    auto scale_f = [&](const uint32_t (&sp)[NP], int gi) -> float {
+        return (gi & 1) ? bf16hi_to_f32(sp[gi >> 1]) : bf16lo_to_f32(sp[gi >> 1]);
+    };
+    // offsets of the wavefront's groups as a B operand: k-slots 0..3 and 4..7 both hold o[g0..g3]
+    // (slots of groups the wavefront does not have are zero and meet zero activation sums)
+    auto offset_operand = [&](const uint32_t (&op)[NP]) -> uint4 {
+        const uint32_t a = op[0], b = NP > 1 ? op[NP - 1] : 0u;
+        return make_uint4(a, b, a, b);
+    };
+
+    // ---- prologue.  Activations first (small, and the first thing the matrix cores need), then the
+    //      codes of the ring and the small inputs.
+    // activations of the wavefront's groups as A operands: lane (m = n, q), MFMA j of group gi holds
+    // x[m][(gw0 + gi) * 128 + q * 32 + j * 8 .. + 8]; rows m >= M and missing groups are zero
+    uint4 xa[GW][4];
+    {
+        const uint16_t* xrow = p.x + (int64_t)min(n, M - 1) * K + q * 32;
+#pragma unroll
+        for (int gi = 0; gi < GW; ++gi)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                xa[gi][j] = *reinterpret_cast<const uint4*>(xrow + (int64_t)group_of(gi) * kGroup + j * 8);
+    }
+    LutLo lut0_lo;
+    uint32_t lut0_hi;
+    if constexpr (AUX) {
+        load_lut(lut0_lo, lut0_hi, t0);                  // the first tile's table comes straight from memory
+#pragma unroll
+        for (int gi = 0; gi < GW; ++gi) cw[0][gi] = *codes_ptr(t0, gi);
+        if (w < kAuxDist && w < ntiles) aux_load(t0 + w);
+#pragma unroll
+        for (int d = 1; d < kDepth; ++d)
+#pragma unroll
+            for (int gi = 0; gi < GW; ++gi) cw[d][gi] = *codes_ptr(min(t0 + d, t1 - 1), gi);
+    } else {
+#pragma unroll
+        for (int d = 0; d < kDepth; ++d) {
+            const int t = min(t0 + d, t1 - 1);
+            load_lut(lut_lo[d], lut_hi[d], t);
+#pragma unroll
+            for (int gi = 0; gi < GW; ++gi) cw[d][gi] = *codes_ptr(t, gi);
+            load_so(sraw[d], oraw[d], t);
+        }
+    }
+    {
+        const bool live_row = n < M;
+#pragma unroll
+        for (int gi = 0; gi < GW; ++gi)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (!(live_row && gi < ngw)) xa[gi][j] = make_uint4(0, 0, 0, 0);
+    }
+    if constexpr (AUX) {
+        build_table(lut0_lo, lut0_hi, 0);
+        if (w < kAuxDist && w < ntiles) aux_write(w);
+    } else {
+        build_table(lut_lo[0], lut_hi[0], 0);
+        load_lut(lut_lo[0], lut_hi[0], min(t0 + kDepth, t1 - 1));
+    }
+
+    // group sums of the activations -> A operand of the offset MFMA (q == 0 lanes: hi parts in
+    // k-slots 0..3, lo parts in k-slots 4..7; other lanes: zero)
+    uint4 xo;
+    {
+        uint32_t hi[4] = {0, 0, 0, 0}, lo[4] = {0, 0, 0, 0};
+#pragma unroll
+        for (int gi = 0; gi < GW; ++gi) {
+            float s = (sum8(xa[gi][0]) + sum8(xa[gi][1])) + (sum8(xa[gi][2]) + sum8(xa[gi][3]));
+            s += __shfl_xor(s, 16);
+            s += __shfl_xor(s, 32);
+            hi[gi] = f32_to_bf16(s);
+            lo[gi] = f32_to_bf16(s - bf16_to_f32(hi[gi]));
+        }
+        xo = make_uint4(hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16), lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16));
+        if (q) xo = make_uint4(0, 0, 0, 0);
+    }
+    if (tid == 0) lastlist[0] = 0;
+    lds_barrier();
+
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+    // the table is the first thing in the block's LDS (the kernel has no static LDS), so a table
+    // offset is an LDS address
+    typedef const __attribute__((address_space(3))) uint32_t* lds_u32;
+    auto lookup = [&](uint32_t wd, uint32_t low) -> uint4 {
+        uint4 b;
+        b.x = *reinterpret_cast<lds_u32>(__builtin_amdgcn_perm(wd, low, 0x0c0c0400u));
+        b.y = *reinterpret_cast<lds_u32>(__builtin_amdgcn_perm(wd, low, 0x0c0c0500u));
+        b.z = *reinterpret_cast<lds_u32>(__builtin_amdgcn_perm(wd, low, 0x0c0c0600u));
+        b.w = *reinterpret_cast<lds_u32>(__builtin_amdgcn_perm(wd, low, 0x0c0c0700u));
+        return b;
+    };
+    auto mfma = [&](const uint4& a, const uint4& b, const f32x4& c) -> f32x4 {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    };
+    const uint32_t low0 = (uint32_t)(n * 8 + (q & 1) * 4);
+
+    // sums the partial results of tile t (left in LDS before the barrier that ended its step) over the
+    // wavefronts in a fixed order and stores them; the wavefronts take turns at this small job
+    auto reduce_store = [&](int t) {
+        const int par = (t - t0) & 1;
+        const int rt = (tid - ((t & (WAVES - 1)) << 6)) & (kThreads - 1);
+        if (rt < M * kTile) {
+            const int m = rt >> 4, nn = rt & 15;
+            const float* src = red + (par * WAVES * 4 + (m & 3)) * 64 + (m >> 2) * 16 + nn;
+            float s = 0.f;
+#pragma unroll
+            for (int ww = 0; ww < WAVES; ++ww) s += src[ww * 4 * 64];
+            const int64_t col = (int64_t)t * kTile + nn;
+            if (col < N) {
+                if (p.slabs == 1) p.y[(int64_t)m * N + col] = (uint16_t)f32_to_bf16(s);
+                else splitk_store(p.partial + ((int64_t)slab * M + m) * N + col, s);
+            }
+        }
+    };
+
+    // ---- one tile.  B = (t - t0) % kDepth is the ring slot of its registers; (t - t0) & 1 selects the
+    //      table and partial-sum buffers.  Order inside a step: the lookups of the first group are
+    //      issued straight after the barrier that completed this tile's table; while they are in
+    //      flight the previous tile's results are summed and stored, the small inputs move on and
+    //      the next tile's table is written; then the groups follow, the lookups of group g+1 always
+    //      issued before the matrix instructions of group g.
+    auto tile_step = [&](auto slot, auto refill, int t) {
+        constexpr int B = decltype(slot)::value, B1 = (B + 1) % kDepth;
+        constexpr bool REFILL = decltype(refill)::value;    // false for the block's last tiles
+        const int i = t - t0, par = i & 1;
+        const int tn = min(t + kDepth, t1 - 1);
+        const uint32_t low = low0 + par * 128;
+        ST_STAMP(0);
+        uint4 bq[2][4];
+        auto lookups = [&](int gi, uint4 (&b)[4]) {
+            const uint4 c = cw[B][gi];
+            b[0] = lookup(c.x, low); b[1] = lookup(c.y, low); b[2] = lookup(c.z, low); b[3] = lookup(c.w, low);
+            if constexpr (REFILL) cw[B][gi] = *codes_ptr(tn, gi);
+        };
+        lookups(0, bq[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        if (i > 0) reduce_store(t - 1);
+        uint32_t sp[NP], op[NP];
+        if constexpr (AUX) {
+            // small inputs: tile i + 2 goes to its LDS slot, tile i + 4 is requested, this tile's
+            // scales and the next tile's table rows are read from their slots
+            if (i + 2 >= kAuxDist && i + 2 < ntiles && w == ((i + 2) & 7)) aux_write((i + 2) & (kAuxDist - 1));
+            if (i + kAuxDist < ntiles && w == ((i + kAuxDist) & 7)) aux_load(t + kAuxDist);
+            aux_read_so(sp, op, i & (kAuxDist - 1));
+            if (i + 1 < ntiles) {
+                LutLo lo;
+                uint32_t hi;
+                aux_read_lut(lo, hi, (i + 1) & (kAuxDist - 1));
+                build_table(lo, hi, par ^ 1);
+            }
+        } else {
+            pack_so(sp, op, sraw[B], oraw[B]);
+            // the table of the next tile goes into the other buffer (everybody finished with it at the
+            // barrier that ended the previous tile); its source registers are then refilled
+            if (i + 1 < ntiles) build_table(lut_lo[B1], lut_hi[B1], par ^ 1);
+            if constexpr (REFILL) load_lut(lut_lo[B1], lut_hi[B1], min(t + 1 + kDepth, t1 - 1));
+        }
+        f32x4 acc = mfma(xo, offset_operand(op), zero);
+#pragma unroll
+        for (int gi = 0; gi < GW; ++gi) {
+            if (gi + 1 < GW) lookups(gi + 1, bq[(gi + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+            const uint4 (&b)[4] = bq[gi & 1];
+            f32x4 P0 = mfma(xa[gi][0], b[0], zero);
+            f32x4 P1 = mfma(xa[gi][1], b[1], zero);
+            P0 = mfma(xa[gi][2], b[2], P0);
+            P1 = mfma(xa[gi][3], b[3], P1);
+            const float sf = scale_f(sp, gi);
+#pragma unroll
+            for (int v = 0; v < 4; ++v) acc[v] = __builtin_fmaf(P0[v] + P1[v], sf, acc[v]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if constexpr (!AUX && REFILL) load_so(sraw[B], oraw[B], tn);
+        // partial sums of this wavefront: accumulator v of lane (n, q) is m = 4 q + v, row n
+        float* rd = red + ((par * WAVES + w) * 4) * 64 + lane;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) rd[v * 64] = acc[v];
+#ifdef ANY4_STAMPS
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        ST_STAMP(1);
+#endif
+        lds_barrier();
+        ST_STAMP(2);
+    };
+
+    // full rounds of the ring in a loop with a single back edge (so that the compiler's count of
+    // outstanding loads at the loop head is exact), then the remaining tiles
+    const int rounds = ntiles / kDepth;
+    int t = t0;
+    using T = std::true_type;
+    using F = std::false_type;
+    for (int it = 0; it < rounds; ++it, t += kDepth) {
+        tile_step(std::integral_constant<int, 0>{}, T{}, t);
+        tile_step(std::integral_constant<int, 1>{}, T{}, t + 1);
+        if constexpr (kDepth == 4) {
+            tile_step(std::integral_constant<int, 2>{}, T{}, t + 2);
+            tile_step(std::integral_constant<int, 3>{}, T{}, t + 3);
+        }
+    }
+    if (t < t1) {
+        tile_step(std::integral_constant<int, 0>{}, F{}, t);
+        if constexpr (kDepth == 4) {
+            if (t + 1 < t1) {
+                tile_step(std::integral_constant<int, 1>{}, F{}, t + 1);
+                if (t + 2 < t1) tile_step(std::integral_constant<int, 2>{}, F{}, t + 2);
+            }
+        }
+    }
+    reduce_store(t1 - 1);
+#ifdef ANY4_STAMPS
+    lds_barrier();
+    if (g_any4_dbg_stream)
+        for (int i = threadIdx.x; i < WAVES * kStampSteps * 4; i += WAVES * 64)
+            g_any4_dbg_stream[(int64_t)blockIdx.x * (16 * kStampSteps * 4) + i] = stamps[i];
+#endif
+
+    // ---- more than one slab: arrive at the counters of all tiles of this block, then finish the
+    //      tiles for which this block was the last
+    if (p.slabs > 1) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's partial sums have been written
+        lds_barrier();                                     // ... and so have the whole block's
+        for (int tb0 = t0; tb0 < t1; tb0 += kListTiles) {      // in rounds of what the list holds
+            const int tb1 = min(t1, tb0 + kListTiles);
+            for (int i = tb0 + tid; i < tb1; i += kThreads) {
+                if (arrive_one(p.counters + i, p.slabs, p.epoch)) {
+                    const int slot = atomicAdd(lastlist, 1);
+                    lastlist[1 + slot] = i;
+                }
+            }
+            lds_barrier();
+            // all outputs of all listed tiles at once, so that the loads of the partial sums overlap
+            const int nlast = lastlist[0];
+            for (int idx = tid; idx < nlast * M * kTile; idx += kThreads) {
+                const int e = idx / (M * kTile), o = idx - e * (M * kTile);
+                const int m = o >> 4, nn = o & 15;
+                const int64_t col = (int64_t)lastlist[1 + e] * kTile + nn;
+                if (col < N) {
+                    float s = 0.f;
+                    for (int k = 0; k < p.slabs; ++k) s += splitk_load(p.partial + ((int64_t)k * M + m) * N + col);
+                    p.y[(int64_t)m * N + col] = (uint16_t)f32_to_bf16(s);
+                }
+            }
+            lds_barrier();
+            if (tid == 0) lastlist[0] = 0;
+            lds_barrier();
+        }
+    }
+}
+
+#ifdef ANY4_STAMPS
+extern "C" int any4_debug_set_buffer_stream(void* p) {
+    long long* q = static_cast<long long*>(p);
+    return (int)hipMemcpyToSymbol(HIP_SYMBOL(g_any4_dbg_stream), &q, sizeof(q));
+}
+#endif
+
+}  // namespace stream
+
+using stream::Params;
+
+// Shape of the work split for a problem; a pure function of (M, N, K) and the number of compute units.
+StreamPlan plan_stream(int64_t M, int64_t N, int64_t K, int cus) {
+    StreamPlan best{};
+    const int G = (int)(K / kGroup);
+    const int64_t tiles = (N + stream::kTile - 1) / stream::kTile;
+    if (M > stream::kTile || tiles > 0x7FFFFFFF) return best;
+    double best_cost = 1e300;
+    int only_gw = 0, only_waves = 0;
+#ifdef ANY4_TUNING
+    if (const char* e = getenv("ANY4_TUNE_GW")) only_gw = atoi(e);
+    if (only_gw < 0) return best;
+    if (const char* e = getenv("ANY4_TUNE_WAVES")) only_waves = atoi(e);
+#endif
+    const bool aux = G % 4 == 0;
+    static const int cand[][2] = {{8, 4}, {8, 2}, {8, 1}, {16, 2}, {16, 1}};      // {wavefronts, groups per wavefront}
+    for (const auto& c : cand) {
+        const int waves = c[0], gw = c[1];
+        if ((only_gw && gw != only_gw) || (only_waves && waves != only_waves)) continue;
+        const int slab_max = waves * gw;
+        int slabs = (G + slab_max - 1) / slab_max;
+        // equal slabs, each a multiple of gw groups (of 4 groups in AUX mode), except possibly the last
+        const int unit = aux ? 4 : gw;
+        const int sgroups = ((G + slabs - 1) / slabs + unit - 1) / unit * unit;
+        if (sgroups > slab_max) continue;
+        slabs = (G + sgroups - 1) / sgroups;
+        if (slabs > kMaxSplit) continue;
+        int bps = cus / slabs;
+        if (bps < 1) bps = 1;
+        if (bps > tiles) bps = (int)tiles;
+        const int64_t tpb = (tiles + bps - 1) / bps;
+        // microseconds: streaming of the block's bytes at ~22 GB/s per compute unit, per-tile
+        // table build and barrier, and the end-of-kernel combination of slabs
+        const double cost = (double)tpb * sgroups * 0.047 + (double)tpb * 0.15 + (slabs > 1 ? 3.0 : 0.0) +
+                            (waves == 16 ? 2.0 : 0.0);
+        if (cost < best_cost) {
+            best_cost = cost;
+            best.waves = waves;
+            best.gw = gw;
+            best.slabs = slabs;
+            best.slab_groups = sgroups;
+            best.blocks_per_slab = bps;
+            best.tiles = tiles;
+            best.aux = aux;
+        }
+    }
+    best.workspace = best.slabs > 1
+        ? splitk_counter_bytes(best.tiles) + (size_t)best.slabs * (size_t)M * (size_t)N * sizeof(float) : 0;
+    return best;
+}
+
+template <int WAVES, int GW, bool AUX>
+static hipError_t launch_stream_t(const Params& p, int grid, hipStream_t stream) {
+    auto kern = stream::decode_stream_kernel<WAVES, GW, AUX>;
+#ifdef ANY4_STAMPS
+    constexpr int lds = stream::lds_bytes(WAVES) + WAVES * stream::kStampSteps * 4 * 8;
+#else
+    constexpr int lds = stream::lds_bytes(WAVES);
+#endif
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(WAVES * 64), lds, stream, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_decode_stream(const uint16_t* x, const uint32_t* codes, const uint16_t* lut,
+                                const uint16_t* scale, const uint16_t* offset, int64_t M, int64_t N,
+                                int64_t K, const StreamPlan& sp, uint16_t* y, void* workspace,
+                                unsigned long long epoch, hipStream_t stream) {
+    Params p{};
+    p.x = x; p.codes = codes; p.lut = lut; p.scale = scale; p.offset = offset; p.y = y;
+    p.counters = static_cast<unsigned long long*>(workspace);
+    p.partial = sp.slabs > 1
+        ? reinterpret_cast<float*>(static_cast<char*>(workspace) + splitk_counter_bytes(sp.tiles)) : nullptr;
+    p.epoch = epoch;
+    p.N = N; p.K = K; p.M = (int)M; p.G = (int)(K / kGroup);
+    p.slabs = sp.slabs; p.slab_groups = sp.slab_groups; p.blocks_per_slab = sp.blocks_per_slab;
+    p.tiles = (int)sp.tiles;
+    const int grid = sp.slabs * sp.blocks_per_slab;
+#define ANY4_STREAM(W, GW)                                                                    \
+    (sp.aux ? launch_stream_t<W, GW, true>(p, grid, stream) : launch_stream_t<W, GW, false>(p, grid, stream))
+    if (sp.waves == 16) return sp.gw == 2 ? ANY4_STREAM(16, 2) : ANY4_STREAM(16, 1);
+    switch (sp.gw) {
+        case 4: return ANY4_STREAM(8, 4);
+        case 2: return ANY4_STREAM(8, 2);
+        default: return ANY4_STREAM(8, 1);
+    }
+#undef ANY4_STREAM
+}
+
+}  // namespace any4
