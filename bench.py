@@ -87,7 +87,8 @@ def main():
         return layer
 
     def launch(g):
-        any4.any4_gemm(g["x"], g["codes"], g["lut"], g["scale"], g["offset"], bits, out=g["y"], workspace=g["ws"])
+        any4.any4_gemm(g["x"], g["codes"], g["lut"], g["scale"], g["offset"], g.get("bits", bits), out=g["y"],
+                       workspace=g["ws"])
 
     if args.copy_calibration:
         a = torch.zeros(1 << 28, dtype=torch.uint8, device=dev)
@@ -225,6 +226,28 @@ def main():
                 del rot
                 torch.cuda.empty_cache()
         extras["llama3_70b"] = big
+        # config 5: 3- and 2-bit variants on the 70B shapes, M = 1 and 16
+        low = {}
+        for b in (3, 2):
+            for i, (name, (N, K)) in enumerate(inputs.LLAMA3_70B_SHAPES.items()):
+                copies = max(2, min(8, int(1.2e9 // (N * K * b // 8)) + 1))
+                for Mx in (1, 16):
+                    rot = []
+                    for c in range(copies):
+                        t = inputs.make_case_device(Mx, N, K, b, seed=inputs.case_seed(500 + c, i), device=dev)
+                        rot.append({"x": t["x"], "codes": any4.any4_pack(t["codes_u8"], b), "lut": t["lut"],
+                                    "scale": t["scale"], "offset": t["offset"], "bits": b,
+                                    "y": torch.empty((Mx, N), dtype=torch.bfloat16, device=dev),
+                                    "ws": torch.empty(max(any4.any4_gemm_workspace_bytes(Mx, N, K, b), 16),
+                                                      dtype=torch.uint8, device=dev)})
+                        del t
+                    us = time_gemm(rot[0], 24, rot)
+                    by = algorithmic_bytes(Mx, N, K, b)
+                    low[f"any{b}_{name}_M{Mx}"] = {"us": us, "GBps": by / (us * 1e-6) / 1e9,
+                                                   "frac_of_hbm_peak": by / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS}
+                    del rot
+                    torch.cuda.empty_cache()
+        extras["llama3_70b_any3_any2"] = low
         layers = [layers_keep]
 
     # ------------------------------------------------------------------ CPU oracle beside it
@@ -251,7 +274,7 @@ def main():
                          f"({sample_bytes / 1e6:.1f} MB algorithmic), {reps} passes, {dt * 1e3:.1f} ms per pass"}
 
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "decode_m1_llama3_8b_hbm_traffic.txt")
+    tpath = os.path.join(ROOT, "profiles", "decode_stream_llama3_8b_m1_hbm_traffic.txt")
     if os.path.exists(tpath):                       # measured offline with rocprofv3 --pmc, see the file
         for line in open(tpath):
             if line.startswith("traffic_bytes_per_launch:"):
@@ -261,14 +284,14 @@ def main():
         "metric": "any4 GEMM achieved HBM GB/s (M=1) on Llama-3-8B shapes",
         "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16 x any4 -> fp32 accumulate -> bf16", "data": "synthetic",
+        "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "Llama-3-8B decode linears (qkv 6144x4096, o 4096x4096, gate_up 28672x4096, "
                                "down 4096x14336), any4 g=128, M=1; step = the four GEMMs of one layer, "
                                f"rotating over {args.layers} distinct layers, HIP-graph replay",
                    "M": 1, "bits": bits, "group": 128, "bytes_per_step": step_bytes},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
-                     "kernel": "any4::decode_m1_kernel (any4 GEMV, M=1)", "avg_launch_us": avg_launch_us,
+                     "kernel": "any4::stream::decode_stream_kernel (any4 GEMM, M<=16; here M=1)", "avg_launch_us": avg_launch_us,
                      "bytes_per_launch": bytes_per_launch},
         "cpu_baseline": cpu,
         "extras": extras,
