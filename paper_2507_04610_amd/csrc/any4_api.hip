@@ -17,7 +17,7 @@ static int shape_check(int64_t N, int64_t K, int bits) {
 }
 
 constexpr int kDecodeMaxM = 16;
-constexpr int kStreamMaxM = 32;
+constexpr int kStreamMaxM = 16;
 
 // Compute units of the current device (256 on MI355X); only shapes the work split, never results.
 int device_compute_units() {
@@ -42,7 +42,7 @@ static unsigned long long next_epoch() {
 
 GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int bits) {
     GemmPlan p{};
-    if (bits == 4 && M <= kStreamMaxM && N <= ((int64_t)1 << 35)) {
+    if (M <= kStreamMaxM && N <= ((int64_t)1 << 35)) {
         p.sp = plan_stream(M, N, K, device_compute_units());
         if (p.sp.gw > 0) {
             p.decode = p.stream = true;
@@ -52,29 +52,8 @@ GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int bits) {
         }
     }
     p.decode = M <= kDecodeMaxM;
-    p.tile = p.decode && bits == 4;
-    p.m1 = p.tile && M == 1 && (K / ANY4_GROUP) % 8 == 0;
     p.ksplit = 1;
-    p.gslice = 0;
-    const int64_t G = K / ANY4_GROUP;
-    if (p.tile) {
-        // blocks of 64 rows x one K slice of `gslice` groups.  Long slices amortise the per-block
-        // table build, so K is split only as far as needed to have about one block per compute
-        // unit; a slice is a multiple of 8 groups (one 2-group chunk per wavefront of a 4-wave
-        // block, and 16-byte aligned scale rows) and never longer than the kernels' LDS budget.
-        const int64_t tiles = (N + 63) / 64;
-        const int64_t want_slices = (256 + tiles - 1) / tiles;
-        int64_t gs = (G + want_slices - 1) / want_slices;
-        gs = (gs + 7) / 8 * 8;
-        const int64_t limit = p.m1 ? decode_m1_gslice_limit() : decode_tile_gslice_limit((int)M);
-        if (gs > limit) gs = limit;
-        if ((G + gs - 1) / gs > kMaxSplit) gs = ((G + kMaxSplit - 1) / kMaxSplit + 7) / 8 * 8;
-#ifdef ANY4_TUNING
-        if (const char* e = getenv("ANY4_TUNE_GSLICE")) gs = atoi(e);
-#endif
-        p.gslice = (int)gs;
-        p.ksplit = (int)((G + gs - 1) / gs);
-    } else if (p.decode) {
+    if (p.decode) {
         // one wavefront per (row, K slice): aim for at least ~8K wavefronts in flight, but keep
         // every slice at least one full 64-lane step long
         const int unit_codes = bits == 4 ? 32 : (bits == 2 ? 64 : 128);
@@ -85,9 +64,7 @@ GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int bits) {
         if (want < 1) want = 1;
         p.ksplit = (int)want;
     }
-    if (p.tile)
-        p.workspace = p.ksplit > 1 ? splitk_counter_bytes((N + 63) / 64) + (size_t)p.ksplit * (size_t)M * (size_t)N * sizeof(float) : 0;
-    else if (p.decode) p.workspace = p.ksplit > 1 ? (size_t)p.ksplit * (size_t)M * (size_t)N * sizeof(float) : 0;
+    if (p.decode) p.workspace = p.ksplit > 1 ? (size_t)p.ksplit * (size_t)M * (size_t)N * sizeof(float) : 0;
     else p.workspace = prefill_workspace_bytes(M, K);
     return p;
 }
@@ -135,12 +112,7 @@ int any4_gemm(const uint16_t* x, const uint32_t* codes, const uint16_t* lut, con
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t e;
     if (plan.stream) {
-        e = launch_decode_stream(x, codes, lut, scale, offset, M, N, K, plan.sp, y, workspace, next_epoch(), s);
-    } else if (plan.tile) {
-        const unsigned long long epoch = next_epoch();
-        e = plan.m1
-            ? launch_decode_m1(x, codes, lut, scale, offset, N, K, plan, y, workspace, epoch, s)
-            : launch_decode_tile(x, codes, lut, scale, offset, M, N, K, plan, y, workspace, epoch, s);
+        e = launch_decode_stream(x, codes, lut, scale, offset, M, N, K, bits, plan.sp, y, workspace, next_epoch(), s);
     } else if (plan.decode) {
         e = launch_decode(x, codes, lut, scale, offset, M, N, K, bits, plan, y, static_cast<float*>(workspace), s);
     } else {

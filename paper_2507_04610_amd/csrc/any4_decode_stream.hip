@@ -1,4 +1,5 @@
-// Memory-bound any4 GEMM for small M (token generation, 1 <= M <= 16): persistent streaming kernel.
+// Memory-bound any-n GEMM (n = 4, 3, 2) for small M (token generation, 1 <= M <= 16): persistent
+// streaming kernel.
 //
 // y[m][n] = sum_k x[m][k] * (LUT[n][code[n][k]] * scale[n][k/128] + offset[n][k/128])
 // (any4 paper, section 4.2 for y = x w^T with on-the-fly dequantisation, sections 2.4.1 and
@@ -47,6 +48,14 @@
 // it needs K/128 to be a multiple of 4 for the 8-byte alignment of its loads, otherwise every
 // wavefront reads what it needs itself).
 //
+// 3- and 2-bit codes (the "anyn" variants of section 4.1) use the same kernel.  A lane's quarter of a
+// group is 12 or 8 bytes instead of 16.  any3: a pair of codes is a 6-bit field of the lane's 96-bit
+// chunk (v_bfe_u32, or v_alignbit_b32 for the two fields that straddle a word) indexing a
+// 64-entry pair table of the same layout.  any2: a byte holds four codes and indexes a 256-entry
+// table of QUADS (four bf16, one ds_read_b64, entry e of row n at LDS byte e * 256 + n * 16 and
+// + 8, second buffer + 64 KB), so a lookup costs the same LDS slot as for any4 and yields four
+// weights.
+//
 // With more than one slab the partial sums go to the workspace and the block that is last to
 // finish a tile adds the slabs in slab order: results do not depend on the order in which
 // blocks run.
@@ -68,16 +77,19 @@ constexpr int kTile = 16;                              // weight rows per tile
 #define ANY4_STREAM_DEPTH 2
 #endif
 constexpr int kDepth = ANY4_STREAM_DEPTH;              // tiles of code loads in flight per wavefront (2 or 4)
-constexpr int kTableBytes = 256 * 256;                 // 256 entries x (2 buffers x 16 rows x 2 copies x 4 B)
+constexpr int kWaves = 8;                              // wavefronts per block: two per SIMD, up to 256 registers each
+// LDS bytes of the two table buffers: any4 256 entries x (2 buffers x 16 rows x 2 copies x 4 B), any3 the
+// same with 64 entries, any2 256 entries x (16 rows x 2 copies x 8 B) per buffer
+constexpr int table_bytes(int bits) { return bits == 4 ? 256 * 256 : (bits == 3 ? 64 * 256 : 2 * 256 * 256); }
 constexpr int kListTiles = 1024;                       // tiles whose slabs a block combines per round
 constexpr int kAuxDist = 4;                            // tiles between the load of a tile's small inputs and their use
 constexpr int kAuxRow = 72;                            // LDS bytes per row of scales (64 + 8 of padding against bank conflicts)
 constexpr int kAuxScale = 0, kAuxOffset = kTile * kAuxRow, kAuxLut = 2 * kTile * kAuxRow;
 constexpr int kAuxSlot = kAuxLut + kTile * 32;         // 2816 B: scales, offsets and tables of one tile
-constexpr int red_bytes(int waves) { return 2 * waves * 4 * 64 * 4; }     // [2][waves][4][64] fp32 partial sums
-constexpr int aux_base(int waves) { return kTableBytes + red_bytes(waves); }
-constexpr int list_base(int waves) { return aux_base(waves) + kAuxDist * kAuxSlot; }
-constexpr int lds_bytes(int waves) { return list_base(waves) + (1 + kListTiles) * 4; }
+constexpr int kRedBytes = 2 * kWaves * 4 * 64 * 4;     // [2][kWaves][4][64] fp32 partial sums
+constexpr int aux_base(int bits) { return table_bytes(bits) + kRedBytes; }
+constexpr int list_base(int bits) { return aux_base(bits) + kAuxDist * kAuxSlot; }
+constexpr int lds_bytes(int bits) { return list_base(bits) + (1 + kListTiles) * 4; }
 
 #ifdef ANY4_STAMPS
 // timing probes for tuning builds: time stamps at the natural LDS synchronisation points of a tile
@@ -132,22 +144,25 @@ __device__ __forceinline__ bool arrive_one(unsigned long long* c, int ksplit, un
     return last;
 }
 
-// WAVES   wavefronts per block: 8 (two per SIMD, up to 256 registers each) or 16 (four per SIMD)
+// BITS    code width: 4, 3 or 2
 // GW      groups (of 128 weights) a wavefront owns: 1, 2 or 4
 // AUX     tables, scales and offsets of a tile are loaded by one wavefront and shared through LDS;
 //         requires K/128 and the slab size to be multiples of 4 (8-byte aligned loads)
-template <int WAVES, int GW, bool AUX>
-__global__ __launch_bounds__(WAVES * 64, 1) void decode_stream_kernel(const Params p) {
-    static_assert(WAVES == 8 || WAVES == 16, "the table build is written for 8 or 16 wavefronts");
+template <int BITS, int GW, bool AUX>
+__global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Params p) {
+    static_assert(BITS == 4 || BITS == 3 || BITS == 2, "code width");
     static_assert(kDepth == 4 || kDepth == 2, "the tile loop is unrolled by kDepth");
-    constexpr int kThreads = WAVES * 64;
+    constexpr int WAVES = kWaves, kThreads = WAVES * 64;
     constexpr int NP = (GW + 1) / 2;                     // packed bf16 pairs holding GW scales
+    constexpr int QW = BITS;                             // 32-bit words of a lane's quarter group (32 codes)
+    constexpr int QB = 4 * BITS, GB = 16 * BITS;         // bytes of a quarter group / of a group, per row
+    constexpr int LUTB = 2 << BITS;                      // bytes of a row's table
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    float* red = reinterpret_cast<float*>(smem + kTableBytes);          // [2][WAVES][4][64]
-    unsigned char* const aux = smem + aux_base(WAVES);                  // [kAuxDist] slots
-    int* lastlist = reinterpret_cast<int*>(smem + list_base(WAVES));    // [0] = count
+    float* red = reinterpret_cast<float*>(smem + table_bytes(BITS));    // [2][WAVES][4][64]
+    unsigned char* const aux = smem + aux_base(BITS);                   // [kAuxDist] slots
+    int* lastlist = reinterpret_cast<int*>(smem + list_base(BITS));     // [0] = count
 #ifdef ANY4_STAMPS
-    long long* stamps = reinterpret_cast<long long*>(smem + lds_bytes(WAVES));
+    long long* stamps = reinterpret_cast<long long*>(smem + lds_bytes(BITS));
     for (int i = threadIdx.x; i < WAVES * kStampSteps * 4; i += WAVES * 64) stamps[i] = 0;
 #endif
 
@@ -177,57 +192,100 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_stream_kernel(const Para
     // past N are clamped to row N - 1 (they are read, never stored); only the lane offsets differ.
     const int last_tile = p.tiles - 1;
     const int nc = min(n, (int)(N - 1 - (int64_t)last_tile * kTile));        // this lane's row inside the last tile
-    const uint32_t row_bytes = (uint32_t)(K / 2);
-    const uint32_t vc_norm = (uint32_t)n * row_bytes + (uint32_t)q * 16u, vc_last = (uint32_t)nc * row_bytes + (uint32_t)q * 16u;
-    const uint32_t vl_norm = (uint32_t)n * 32u, vl_last = (uint32_t)nc * 32u;
+    const uint32_t row_bytes = (uint32_t)(K * BITS / 8);
+    const uint32_t vc_norm = (uint32_t)n * row_bytes + (uint32_t)q * QB, vc_last = (uint32_t)nc * row_bytes + (uint32_t)q * QB;
+    const uint32_t vl_norm = (uint32_t)n * LUTB, vl_last = (uint32_t)nc * LUTB;
     const uint32_t vs_norm = (uint32_t)n * (uint32_t)G * 2u, vs_last = (uint32_t)nc * (uint32_t)G * 2u;
     const char* const codes_b = reinterpret_cast<const char*>(p.codes);
     const char* const lut_b = reinterpret_cast<const char*>(p.lut);
     const char* const scale_b = reinterpret_cast<const char*>(p.scale);
     const char* const offset_b = reinterpret_cast<const char*>(p.offset);
 
-    // ---- codes: a ring of kDepth register sets indexed by (tile - t0) % kDepth
-    uint4 cw[kDepth][GW];
-    auto codes_ptr = [&](int t, int gi) -> const uint4* {
-        const char* base = codes_b + (int64_t)t * (kTile * (int64_t)row_bytes) + group_of(gi) * 64;
-        return reinterpret_cast<const uint4*>(base + (t == last_tile ? vc_last : vc_norm));
+    // ---- codes: a ring of kDepth register sets indexed by (tile - t0) % kDepth; one lane holds the
+    //      QW words of its quarter of each of the wavefront's groups
+    struct Quarter { uint32_t w[QW]; };
+    Quarter cw[kDepth][GW];
+    auto load_codes = [&](Quarter& c, int t, int gi) {
+        const char* base = codes_b + (int64_t)t * (kTile * (int64_t)row_bytes) + group_of(gi) * GB;
+        const char* a = base + (t == last_tile ? vc_last : vc_norm);
+        if constexpr (BITS == 4) {
+            const uint4 v = *reinterpret_cast<const uint4*>(a);
+            c.w[0] = v.x; c.w[1] = v.y; c.w[2] = v.z; c.w[3] = v.w;
+        } else if constexpr (BITS == 3) {
+            typedef uint32_t u32x3 __attribute__((ext_vector_type(3), aligned(4)));
+            const u32x3 v = *reinterpret_cast<const u32x3*>(a);
+            c.w[0] = v.x; c.w[1] = v.y; c.w[2] = v.z;
+        } else {
+            const uint2 v = *reinterpret_cast<const uint2*>(a);
+            c.w[0] = v.x; c.w[1] = v.y;
+        }
     };
 
-    // ---- table source of a tile.  The 256 entries of a row are written by its 4 * WAVES threads:
-    //   8 wavefronts: thread (w, n, q) writes high nibble 2w + q/2, low nibbles 8 (q % 2) .. + 8
-    //  16 wavefronts: thread (w, n, q) writes high nibble w,        low nibbles 4 q .. + 4
-    // so it needs that part of the row's table and the dword that holds LUT[hi].
-    using LutLo = std::conditional_t<WAVES == 8, uint4, uint2>;
-    const uint32_t lut_lo_off = WAVES == 8 ? (uint32_t)(q & 1) * 16u : (uint32_t)q * 8u;
-    const uint32_t lut_hi_off = WAVES == 8 ? (uint32_t)w * 4u : (uint32_t)(w >> 1) * 4u;
-    auto load_lut = [&](LutLo& lo, uint32_t& hi, int t) {          // straight from memory
-        const char* base = lut_b + (int64_t)t * (kTile * 32);
-        const uint32_t v = t == last_tile ? vl_last : vl_norm;
-        lo = *reinterpret_cast<const LutLo*>(base + (v + lut_lo_off));
-        hi = *reinterpret_cast<const uint32_t*>(base + lut_hi_off + v);
+    // ---- table source of a tile.  The entries of a row are written by its 32 threads (w, q):
+    //   any4: 256 pair entries (hi << 4 | lo): thread writes hi = 2w + q/2, lo = 8 (q % 2) .. + 8
+    //   any3:  64 pair entries (hi << 3 | lo): thread writes hi = w,        lo = 2q, 2q + 1
+    //   any2: 256 quad entries (c3 c2 c1 c0):  thread writes entries 8 (4w + q) .. + 8
+    // LutSrc holds the part of the row's table a thread needs for that: any4 its half row (4 words) and
+    // the word with LUT[hi]; any3 word q and the word with LUT[w]; any2 the whole row (2 words).
+    struct LutSrc { uint32_t a[BITS == 4 ? 4 : (BITS == 3 ? 1 : 2)]; uint32_t h; };
+    const uint32_t lut_lo_off = BITS == 4 ? (uint32_t)(q & 1) * 16u : (BITS == 3 ? (uint32_t)q * 4u : 0u);
+    const uint32_t lut_hi_off = BITS == 4 ? (uint32_t)w * 4u : (uint32_t)(w >> 1) * 4u;
+    // reads a LutSrc from a row of the table, in memory or in an LDS slot (same code, any pointer)
+    auto read_lut_row = [&](LutSrc& l, const char* row) {
+        if constexpr (BITS == 4) {
+            const uint4 v = *reinterpret_cast<const uint4*>(row + lut_lo_off);
+            l.a[0] = v.x; l.a[1] = v.y; l.a[2] = v.z; l.a[3] = v.w;
+            l.h = *reinterpret_cast<const uint32_t*>(row + lut_hi_off);
+        } else if constexpr (BITS == 3) {
+            l.a[0] = *reinterpret_cast<const uint32_t*>(row + lut_lo_off);
+            l.h = *reinterpret_cast<const uint32_t*>(row + lut_hi_off);
+        } else {
+            const uint2 v = *reinterpret_cast<const uint2*>(row);
+            l.a[0] = v.x; l.a[1] = v.y; l.h = 0;
+        }
     };
-    // table of a tile into buffer `par`: entry e of row n at dword e * 64 + par * 32 + n * 2, both copies
-    const int hi_nib = WAVES == 8 ? 2 * w + (q >> 1) : w, lo_nib0 = WAVES == 8 ? 8 * (q & 1) : 4 * q;
-    uint32_t* const tdst = reinterpret_cast<uint32_t*>(smem) + (hi_nib * 16 + lo_nib0) * 64 + n * 2;
-    auto build_table = [&](const LutLo& lo, uint32_t hi, int par) {
-        uint32_t hv;
-        if constexpr (WAVES == 8) hv = (q & 2) ? (hi & 0xFFFF0000u) : (hi << 16);
-        else hv = (w & 1) ? (hi & 0xFFFF0000u) : (hi << 16);
-        uint32_t* dst = tdst + par * 32;
-        constexpr int NE = WAVES == 8 ? 8 : 4;
-        uint32_t L[NE / 2];
-        if constexpr (WAVES == 8) { L[0] = lo.x; L[1] = lo.y; L[2] = lo.z; L[3] = lo.w; }
-        else { L[0] = lo.x; L[1] = lo.y; }
+    auto load_lut = [&](LutSrc& l, int t) {          // straight from memory
+        read_lut_row(l, lut_b + (int64_t)t * (kTile * LUTB) + (t == last_tile ? vl_last : vl_norm));
+    };
+    // table of a tile into buffer `par`
+    auto build_table = [&](const LutSrc& l, int par) {
+        uint32_t* const tab = reinterpret_cast<uint32_t*>(smem);
+        if constexpr (BITS == 4) {
+            // entry e of row n at dword e * 64 + par * 32 + n * 2, both copies
+            const uint32_t hv = (q & 2) ? (l.h & 0xFFFF0000u) : (l.h << 16);
+            uint32_t* dst = tab + ((2 * w + (q >> 1)) * 16 + 8 * (q & 1)) * 64 + par * 32 + n * 2;
 #pragma unroll
-        for (int i = 0; i < NE; ++i) {
-            const uint32_t lv = (i & 1) ? (L[i >> 1] >> 16) : (L[i >> 1] & 0xFFFFu);
-            *reinterpret_cast<uint2*>(dst + i * 64) = make_uint2(lv | hv, lv | hv);
+            for (int i = 0; i < 8; ++i) {
+                const uint32_t lv = (i & 1) ? (l.a[i >> 1] >> 16) : (l.a[i >> 1] & 0xFFFFu);
+                *reinterpret_cast<uint2*>(dst + i * 64) = make_uint2(lv | hv, lv | hv);
+            }
+        } else if constexpr (BITS == 3) {
+            const uint32_t hv = (w & 1) ? (l.h & 0xFFFF0000u) : (l.h << 16);
+            uint32_t* dst = tab + (w * 8 + 2 * q) * 64 + par * 32 + n * 2;
+            const uint32_t v0 = (l.a[0] & 0xFFFFu) | hv, v1 = (l.a[0] >> 16) | hv;
+            *reinterpret_cast<uint2*>(dst) = make_uint2(v0, v0);
+            *reinterpret_cast<uint2*>(dst + 64) = make_uint2(v1, v1);
+        } else {
+            // entry e of row n at dword e * 64 + par * 16384 + n * 4, both copies (16 bytes)
+            auto val = [&](int c) -> uint32_t { return ((c & 2) ? l.a[1] : l.a[0]) >> (16 * (c & 1)) & 0xFFFFu; };
+            auto valv = [&](uint32_t c) -> uint32_t {            // lane-dependent index
+                const uint32_t d = (c & 2u) ? l.a[1] : l.a[0];
+                return (c & 1u) ? (d >> 16) : (d & 0xFFFFu);
+            };
+            const uint32_t d1 = valv(((uint32_t)(w & 1) << 1) | (uint32_t)(q >> 1)) | (valv((uint32_t)(w >> 1)) << 16);
+            uint32_t* dst = tab + ((4 * w + q) * 8) * 64 + par * 16384 + n * 4;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const uint32_t d0 = val(i & 3) | (valv(((uint32_t)(q & 1) << 1) | (uint32_t)(i >> 2)) << 16);
+                *reinterpret_cast<uint4*>(dst + i * 64) = make_uint4(d0, d1, d0, d1);
+            }
         }
     };
 
     // ---- AUX mode: the tile's scales, offsets and tables, loaded by one wavefront into registers
-    //      (lane (n, j): scale / offset groups 4j .. 4j+3 and 16 + 4j .. 16 + 4j+3 of the slab; lanes
-    //      with j < 2: half j of the row's table) and written to an LDS slot two tiles later
+    //      (lane (n, j): scale / offset groups 4j .. 4j+3 and 16 + 4j .. 16 + 4j+3 of the slab; the
+    //      row's table by lanes j < 2 (any4, 16 bytes each) or j = 0 (any3: 16 bytes, any2: 8)) and
+    //      written to an LDS slot two tiles later.  Table rows keep a 32-byte stride in the slot.
     uint2 axs[2], axo[2];
     uint4 axl;
     auto aux_load = [&](int t) {
@@ -239,8 +297,10 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_stream_kernel(const Para
                 axs[c] = *reinterpret_cast<const uint2*>(scale_b + tile_off + c * 32 + vs);
                 axo[c] = *reinterpret_cast<const uint2*>(offset_b + tile_off + c * 32 + vs);
             }
-        if (q < 2)
-            axl = *reinterpret_cast<const uint4*>(lut_b + (int64_t)t * (kTile * 32) + ((t == last_tile ? vl_last : vl_norm) + (uint32_t)q * 16u));
+        const char* lrow = lut_b + (int64_t)t * (kTile * LUTB) + (t == last_tile ? vl_last : vl_norm);
+        if constexpr (BITS == 4) { if (q < 2) axl = *reinterpret_cast<const uint4*>(lrow + q * 16); }
+        else if constexpr (BITS == 3) { if (q < 1) axl = *reinterpret_cast<const uint4*>(lrow); }
+        else { if (q < 1) { const uint2 v = *reinterpret_cast<const uint2*>(lrow); axl.x = v.x; axl.y = v.y; } }
     };
     auto aux_write = [&](int slot) {
         unsigned char* s = aux + slot * kAuxSlot;
@@ -250,12 +310,12 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_stream_kernel(const Para
                 *reinterpret_cast<uint2*>(s + kAuxScale + n * kAuxRow + (c * 4 + q) * 8) = axs[c];
                 *reinterpret_cast<uint2*>(s + kAuxOffset + n * kAuxRow + (c * 4 + q) * 8) = axo[c];
             }
-        if (q < 2) *reinterpret_cast<uint4*>(s + kAuxLut + n * 32 + q * 16) = axl;
+        if constexpr (BITS == 4) { if (q < 2) *reinterpret_cast<uint4*>(s + kAuxLut + n * 32 + q * 16) = axl; }
+        else if constexpr (BITS == 3) { if (q < 1) *reinterpret_cast<uint4*>(s + kAuxLut + n * 32) = axl; }
+        else { if (q < 1) *reinterpret_cast<uint2*>(s + kAuxLut + n * 32) = make_uint2(axl.x, axl.y); }
     };
-    auto aux_read_lut = [&](LutLo& lo, uint32_t& hi, int slot) {
-        const unsigned char* s = aux + slot * kAuxSlot + kAuxLut + n * 32;
-        lo = *reinterpret_cast<const LutLo*>(s + lut_lo_off);
-        hi = *reinterpret_cast<const uint32_t*>(s + lut_hi_off);
+    auto aux_read_lut = [&](LutSrc& l, int slot) {
+        read_lut_row(l, reinterpret_cast<const char*>(aux + slot * kAuxSlot + kAuxLut + n * 32));
     };
 
     // ---- scales and offsets of the wavefront's groups for one tile, as packed bf16 pairs
@@ -280,8 +340,7 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_stream_kernel(const Para
     // without AUX: every wavefront reads its own scales, offsets (one bf16 per load) and table rows,
     // in rings like the codes
     uint32_t sraw[kDepth][GW], oraw[kDepth][GW];
-    LutLo lut_lo[kDepth];
-    uint32_t lut_hi[kDepth];
+    LutSrc lut_ring[kDepth];
     auto load_so = [&](uint32_t (&sr)[GW], uint32_t (&orw)[GW], int t) {
         const int64_t tile_off = (int64_t)t * (kTile * 2) * G;
         const uint32_t v = t == last_tile ? vs_last : vs_norm;
@@ -321,24 +380,23 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_stream_kernel(const Para
             for (int j = 0; j < 4; ++j)
                 xa[gi][j] = *reinterpret_cast<const uint4*>(xrow + (int64_t)group_of(gi) * kGroup + j * 8);
     }
-    LutLo lut0_lo;
-    uint32_t lut0_hi;
+    LutSrc lut0;
     if constexpr (AUX) {
-        load_lut(lut0_lo, lut0_hi, t0);                  // the first tile's table comes straight from memory
+        load_lut(lut0, t0);                              // the first tile's table comes straight from memory
 #pragma unroll
-        for (int gi = 0; gi < GW; ++gi) cw[0][gi] = *codes_ptr(t0, gi);
+        for (int gi = 0; gi < GW; ++gi) load_codes(cw[0][gi], t0, gi);
         if (w < kAuxDist && w < ntiles) aux_load(t0 + w);
 #pragma unroll
         for (int d = 1; d < kDepth; ++d)
 #pragma unroll
-            for (int gi = 0; gi < GW; ++gi) cw[d][gi] = *codes_ptr(min(t0 + d, t1 - 1), gi);
+            for (int gi = 0; gi < GW; ++gi) load_codes(cw[d][gi], min(t0 + d, t1 - 1), gi);
     } else {
 #pragma unroll
         for (int d = 0; d < kDepth; ++d) {
             const int t = min(t0 + d, t1 - 1);
-            load_lut(lut_lo[d], lut_hi[d], t);
+            load_lut(lut_ring[d], t);
 #pragma unroll
-            for (int gi = 0; gi < GW; ++gi) cw[d][gi] = *codes_ptr(t, gi);
+            for (int gi = 0; gi < GW; ++gi) load_codes(cw[d][gi], t, gi);
             load_so(sraw[d], oraw[d], t);
         }
     }
@@ -351,11 +409,11 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_stream_kernel(const Para
                 if (!(live_row && gi < ngw)) xa[gi][j] = make_uint4(0, 0, 0, 0);
     }
     if constexpr (AUX) {
-        build_table(lut0_lo, lut0_hi, 0);
+        build_table(lut0, 0);
         if (w < kAuxDist && w < ntiles) aux_write(w);
     } else {
-        build_table(lut_lo[0], lut_hi[0], 0);
-        load_lut(lut_lo[0], lut_hi[0], min(t0 + kDepth, t1 - 1));
+        build_table(lut_ring[0], 0);
+        load_lut(lut_ring[0], min(t0 + kDepth, t1 - 1));
     }
 
     // group sums of the activations -> A operand of the offset MFMA (q == 0 lanes: hi parts in
@@ -378,21 +436,45 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_stream_kernel(const Para
     lds_barrier();
 
     const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-    // the table is the first thing in the block's LDS (the kernel has no static LDS), so a table
+    // the tables are the first thing in the block's LDS (the kernel has no static LDS), so a table
     // offset is an LDS address
     typedef const __attribute__((address_space(3))) uint32_t* lds_u32;
-    auto lookup = [&](uint32_t wd, uint32_t low) -> uint4 {
+    typedef const __attribute__((address_space(3))) unsigned long long* lds_u64;
+    // B operand of MFMA j (codes 8j .. 8j+7 of the lane's quarter) of one quarter group.
+    // `low` = the lane's fixed part of a table address (row, copy and table buffer).
+    auto lookup = [&](const Quarter& c, int j, uint32_t low) -> uint4 {
         uint4 b;
-        b.x = *reinterpret_cast<lds_u32>(__builtin_amdgcn_perm(wd, low, 0x0c0c0400u));
-        b.y = *reinterpret_cast<lds_u32>(__builtin_amdgcn_perm(wd, low, 0x0c0c0500u));
-        b.z = *reinterpret_cast<lds_u32>(__builtin_amdgcn_perm(wd, low, 0x0c0c0600u));
-        b.w = *reinterpret_cast<lds_u32>(__builtin_amdgcn_perm(wd, low, 0x0c0c0700u));
+        if constexpr (BITS == 4) {
+            const uint32_t wd = c.w[j];
+            b.x = *reinterpret_cast<lds_u32>(__builtin_amdgcn_perm(wd, low, 0x0c0c0400u));
+            b.y = *reinterpret_cast<lds_u32>(__builtin_amdgcn_perm(wd, low, 0x0c0c0500u));
+            b.z = *reinterpret_cast<lds_u32>(__builtin_amdgcn_perm(wd, low, 0x0c0c0600u));
+            b.w = *reinterpret_cast<lds_u32>(__builtin_amdgcn_perm(wd, low, 0x0c0c0700u));
+        } else if constexpr (BITS == 3) {
+            uint32_t r[4];
+#pragma unroll
+            for (int pi = 0; pi < 4; ++pi) {
+                const int o = 24 * j + 6 * pi, wi = o >> 5, sh = o & 31;
+                uint32_t idx;
+                if (sh <= 26) idx = __builtin_amdgcn_ubfe(c.w[wi], sh, 6);
+                else idx = __builtin_amdgcn_alignbit(c.w[wi + 1 < QW ? wi + 1 : wi], c.w[wi], sh) & 63u;
+                r[pi] = *reinterpret_cast<lds_u32>((idx << 8) | low);
+            }
+            b = make_uint4(r[0], r[1], r[2], r[3]);
+        } else {
+            const uint32_t wd = c.w[j >> 1];
+            const unsigned long long q0 = *reinterpret_cast<lds_u64>(__builtin_amdgcn_perm(wd, low, (j & 1) ? 0x0c020600u : 0x0c020400u));
+            const unsigned long long q1 = *reinterpret_cast<lds_u64>(__builtin_amdgcn_perm(wd, low, (j & 1) ? 0x0c020700u : 0x0c020500u));
+            b = make_uint4((uint32_t)q0, (uint32_t)(q0 >> 32), (uint32_t)q1, (uint32_t)(q1 >> 32));
+        }
         return b;
     };
     auto mfma = [&](const uint4& a, const uint4& b, const f32x4& c) -> f32x4 {
         return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
     };
-    const uint32_t low0 = (uint32_t)(n * 8 + (q & 1) * 4);
+    // lane part of a table address for table buffer 0 / its increment for buffer 1
+    const uint32_t low0 = BITS == 2 ? (uint32_t)(n * 16 + (q & 1) * 8) : (uint32_t)(n * 8 + (q & 1) * 4);
+    constexpr uint32_t kLowPar = BITS == 2 ? 65536u : 128u;
 
     // sums the partial results of tile t (left in LDS before the barrier that ended its step) over the
     // wavefronts in a fixed order and stores them; the wavefronts take turns at this small job
@@ -424,13 +506,13 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_stream_kernel(const Para
         constexpr bool REFILL = decltype(refill)::value;    // false for the block's last tiles
         const int i = t - t0, par = i & 1;
         const int tn = min(t + kDepth, t1 - 1);
-        const uint32_t low = low0 + par * 128;
+        const uint32_t low = low0 + par * kLowPar;
         ST_STAMP(0);
         uint4 bq[2][4];
         auto lookups = [&](int gi, uint4 (&b)[4]) {
-            const uint4 c = cw[B][gi];
-            b[0] = lookup(c.x, low); b[1] = lookup(c.y, low); b[2] = lookup(c.z, low); b[3] = lookup(c.w, low);
-            if constexpr (REFILL) cw[B][gi] = *codes_ptr(tn, gi);
+            const Quarter c = cw[B][gi];
+            b[0] = lookup(c, 0, low); b[1] = lookup(c, 1, low); b[2] = lookup(c, 2, low); b[3] = lookup(c, 3, low);
+            if constexpr (REFILL) load_codes(cw[B][gi], tn, gi);
         };
         lookups(0, bq[0]);
         __builtin_amdgcn_sched_barrier(0);
@@ -443,17 +525,16 @@ __global__ __launch_bounds__(WAVES * 64, 1) void decode_stream_kernel(const Para
             if (i + kAuxDist < ntiles && w == ((i + kAuxDist) & 7)) aux_load(t + kAuxDist);
             aux_read_so(sp, op, i & (kAuxDist - 1));
             if (i + 1 < ntiles) {
-                LutLo lo;
-                uint32_t hi;
-                aux_read_lut(lo, hi, (i + 1) & (kAuxDist - 1));
-                build_table(lo, hi, par ^ 1);
+                LutSrc l;
+                aux_read_lut(l, (i + 1) & (kAuxDist - 1));
+                build_table(l, par ^ 1);
             }
         } else {
             pack_so(sp, op, sraw[B], oraw[B]);
             // the table of the next tile goes into the other buffer (everybody finished with it at the
             // barrier that ended the previous tile); its source registers are then refilled
-            if (i + 1 < ntiles) build_table(lut_lo[B1], lut_hi[B1], par ^ 1);
-            if constexpr (REFILL) load_lut(lut_lo[B1], lut_hi[B1], min(t + 1 + kDepth, t1 - 1));
+            if (i + 1 < ntiles) build_table(lut_ring[B1], par ^ 1);
+            if constexpr (REFILL) load_lut(lut_ring[B1], min(t + 1 + kDepth, t1 - 1));
         }
         f32x4 acc = mfma(xo, offset_operand(op), zero);
 #pragma unroll
@@ -565,18 +646,15 @@ StreamPlan plan_stream(int64_t M, int64_t N, int64_t K, int cus) {
     const int64_t tiles = (N + stream::kTile - 1) / stream::kTile;
     if (M > stream::kTile || tiles > 0x7FFFFFFF) return best;
     double best_cost = 1e300;
-    int only_gw = 0, only_waves = 0;
+    int only_gw = 0;
 #ifdef ANY4_TUNING
     if (const char* e = getenv("ANY4_TUNE_GW")) only_gw = atoi(e);
     if (only_gw < 0) return best;
-    if (const char* e = getenv("ANY4_TUNE_WAVES")) only_waves = atoi(e);
 #endif
     const bool aux = G % 4 == 0;
-    static const int cand[][2] = {{8, 4}, {8, 2}, {8, 1}, {16, 2}, {16, 1}};      // {wavefronts, groups per wavefront}
-    for (const auto& c : cand) {
-        const int waves = c[0], gw = c[1];
-        if ((only_gw && gw != only_gw) || (only_waves && waves != only_waves)) continue;
-        const int slab_max = waves * gw;
+    for (int gw : {4, 2, 1}) {
+        if (only_gw && gw != only_gw) continue;
+        const int slab_max = stream::kWaves * gw;
         int slabs = (G + slab_max - 1) / slab_max;
         // equal slabs, each a multiple of gw groups (of 4 groups in AUX mode), except possibly the last
         const int unit = aux ? 4 : gw;
@@ -590,11 +668,9 @@ StreamPlan plan_stream(int64_t M, int64_t N, int64_t K, int cus) {
         const int64_t tpb = (tiles + bps - 1) / bps;
         // microseconds: streaming of the block's bytes at ~22 GB/s per compute unit, per-tile
         // table build and barrier, and the end-of-kernel combination of slabs
-        const double cost = (double)tpb * sgroups * 0.047 + (double)tpb * 0.15 + (slabs > 1 ? 3.0 : 0.0) +
-                            (waves == 16 ? 2.0 : 0.0);
+        const double cost = (double)tpb * sgroups * 0.047 + (double)tpb * 0.15 + (slabs > 1 ? 3.0 : 0.0);
         if (cost < best_cost) {
             best_cost = cost;
-            best.waves = waves;
             best.gw = gw;
             best.slabs = slabs;
             best.slab_groups = sgroups;
@@ -608,24 +684,36 @@ StreamPlan plan_stream(int64_t M, int64_t N, int64_t K, int cus) {
     return best;
 }
 
-template <int WAVES, int GW, bool AUX>
+template <int BITS, int GW, bool AUX>
 static hipError_t launch_stream_t(const Params& p, int grid, hipStream_t stream) {
-    auto kern = stream::decode_stream_kernel<WAVES, GW, AUX>;
+    auto kern = stream::decode_stream_kernel<BITS, GW, AUX>;
 #ifdef ANY4_STAMPS
-    constexpr int lds = stream::lds_bytes(WAVES) + WAVES * stream::kStampSteps * 4 * 8;
+    constexpr int lds = stream::lds_bytes(BITS) + stream::kWaves * stream::kStampSteps * 4 * 8;
 #else
-    constexpr int lds = stream::lds_bytes(WAVES);
+    constexpr int lds = stream::lds_bytes(BITS);
 #endif
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(WAVES * 64), lds, stream, p);
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(stream::kWaves * 64), lds, stream, p);
     return hipGetLastError();
+}
+
+template <int BITS>
+static hipError_t launch_stream_b(const Params& p, const StreamPlan& sp, int grid, hipStream_t stream) {
+#define ANY4_STREAM(GW)                                                                    \
+    (sp.aux ? launch_stream_t<BITS, GW, true>(p, grid, stream) : launch_stream_t<BITS, GW, false>(p, grid, stream))
+    switch (sp.gw) {
+        case 4: return ANY4_STREAM(4);
+        case 2: return ANY4_STREAM(2);
+        default: return ANY4_STREAM(1);
+    }
+#undef ANY4_STREAM
 }
 
 hipError_t launch_decode_stream(const uint16_t* x, const uint32_t* codes, const uint16_t* lut,
                                 const uint16_t* scale, const uint16_t* offset, int64_t M, int64_t N,
-                                int64_t K, const StreamPlan& sp, uint16_t* y, void* workspace,
+                                int64_t K, int bits, const StreamPlan& sp, uint16_t* y, void* workspace,
                                 unsigned long long epoch, hipStream_t stream) {
     Params p{};
     p.x = x; p.codes = codes; p.lut = lut; p.scale = scale; p.offset = offset; p.y = y;
@@ -637,15 +725,9 @@ hipError_t launch_decode_stream(const uint16_t* x, const uint32_t* codes, const 
     p.slabs = sp.slabs; p.slab_groups = sp.slab_groups; p.blocks_per_slab = sp.blocks_per_slab;
     p.tiles = (int)sp.tiles;
     const int grid = sp.slabs * sp.blocks_per_slab;
-#define ANY4_STREAM(W, GW)                                                                    \
-    (sp.aux ? launch_stream_t<W, GW, true>(p, grid, stream) : launch_stream_t<W, GW, false>(p, grid, stream))
-    if (sp.waves == 16) return sp.gw == 2 ? ANY4_STREAM(16, 2) : ANY4_STREAM(16, 1);
-    switch (sp.gw) {
-        case 4: return ANY4_STREAM(8, 4);
-        case 2: return ANY4_STREAM(8, 2);
-        default: return ANY4_STREAM(8, 1);
-    }
-#undef ANY4_STREAM
+    if (bits == 4) return launch_stream_b<4>(p, sp, grid, stream);
+    if (bits == 3) return launch_stream_b<3>(p, sp, grid, stream);
+    return launch_stream_b<2>(p, sp, grid, stream);
 }
 
 }  // namespace any4

@@ -8,12 +8,11 @@ namespace any4 {
 
 // Work split of the persistent streaming decode kernel (any4_decode_stream.hip).
 struct StreamPlan {
-    int waves;            // wavefronts per block: 8 or 16
     int gw;               // groups per wavefront (0: the kernel cannot take this problem)
     int slabs;            // K slabs, each owned by `blocks_per_slab` blocks
     int slab_groups;      // groups per slab
     int blocks_per_slab;
-    int64_t tiles;        // 32-row tiles
+    int64_t tiles;        // 16-row tiles
     bool aux;             // tables, scales and offsets are shared through LDS (K/128 multiple of 4)
     size_t workspace;     // bytes: tile counters + fp32 partial sums (several slabs only)
 };
@@ -24,12 +23,9 @@ int device_compute_units();
 // any4_gemm_workspace_bytes() and any4_gemm() always agree.
 struct GemmPlan {
     bool decode;          // true: memory-bound small-M kernel, false: matrix-core kernel
-    bool stream;          // decode only: persistent streaming kernel (any4, M <= 32)
+    bool stream;          // decode only: persistent streaming kernel; false: one wavefront per (row, K slice)
     StreamPlan sp;
-    bool tile;            // decode only: row-tile (pair table + MFMA) kernel instead of wave-per-row
-    bool m1;              // decode only: M == 1 lane-per-row (pair table + dot2) kernel
     int ksplit;           // number of K slices whose fp32 partials are reduced in a 2nd pass
-    int gslice;           // row-tile kernel: groups (of 128 weights) per K slice
     size_t workspace;     // bytes of scratch: K-slice partials (decode) or group sums of x (matrix-core path)
 };
 GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int bits);
@@ -43,21 +39,11 @@ hipError_t launch_decode(const uint16_t* x, const uint32_t* codes, const uint16_
                          const uint16_t* scale, const uint16_t* offset,
                          int64_t M, int64_t N, int64_t K, int bits, const GemmPlan& plan,
                          uint16_t* y, float* partial, hipStream_t stream);
-hipError_t launch_decode_tile(const uint16_t* x, const uint32_t* codes, const uint16_t* lut,
-                              const uint16_t* scale, const uint16_t* offset, int64_t M, int64_t N,
-                              int64_t K, const GemmPlan& plan, uint16_t* y, void* workspace,
-                              unsigned long long epoch, hipStream_t stream);
-hipError_t launch_decode_m1(const uint16_t* x, const uint32_t* codes, const uint16_t* lut,
-                            const uint16_t* scale, const uint16_t* offset, int64_t N, int64_t K,
-                            const GemmPlan& plan, uint16_t* y, void* workspace, unsigned long long epoch,
-                            hipStream_t stream);
 hipError_t launch_decode_stream(const uint16_t* x, const uint32_t* codes, const uint16_t* lut,
                                 const uint16_t* scale, const uint16_t* offset, int64_t M, int64_t N,
-                                int64_t K, const StreamPlan& sp, uint16_t* y, void* workspace,
+                                int64_t K, int bits, const StreamPlan& sp, uint16_t* y, void* workspace,
                                 unsigned long long epoch, hipStream_t stream);
 hipError_t launch_reduce_slices(const float* partial, int ksplit, int64_t MN, uint16_t* y, hipStream_t stream);
-int decode_tile_gslice_limit(int M);
-int decode_m1_gslice_limit();
 hipError_t launch_prefill(const uint16_t* x, const uint32_t* codes, const uint16_t* lut,
                           const uint16_t* scale, const uint16_t* offset,
                           int64_t M, int64_t N, int64_t K, int bits,

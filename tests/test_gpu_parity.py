@@ -132,6 +132,22 @@ def test_gemm_prefill_small(any4, oracle, bits, M, N, K):
     run_gemm_case(any4, oracle, M, N, K, bits, seed=inputs.case_seed(5, bits, M % 10))
 
 
+@pytest.mark.parametrize("bits", (4, 3, 2))
+def test_gemm_decode_very_long_k(any4, oracle, bits):
+    """K so long that the streaming kernel's slab count exceeds its limit: the wavefront-per-row
+    kernel with a second-stage reduction takes over."""
+    run_gemm_case(any4, oracle, 2, 5, 262272, bits, seed=inputs.case_seed(6, bits))
+
+
+@pytest.mark.parametrize("bits", (4, 3, 2))
+@pytest.mark.parametrize("M,N,K", [(1, 16, 128), (3, 17, 384), (16, 100, 4480), (7, 4100, 512), (5, 48, 14336),
+                                   (16, 33, 8192), (2, 700, 640)])
+def test_gemm_decode_slabs_and_ragged_groups(any4, oracle, bits, M, N, K):
+    """Streaming kernel: group counts that are / are not multiples of 4 (shared small inputs on and
+    off), wavefronts without groups, several slabs, ragged last tile, more tiles than blocks."""
+    run_gemm_case(any4, oracle, M, N, K, bits, seed=inputs.case_seed(7, bits, M))
+
+
 def test_gemm_zero_offset_and_unsorted_table(any4, oracle):
     def mutate(cs):
         cs.offset[:] = 0                                   # symmetric scaling: beta = 0
