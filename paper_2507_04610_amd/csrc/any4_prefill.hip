@@ -16,17 +16,22 @@
 // dimension whose left operand X is precomputed in fp32 and split into a bf16 high and low part
 // (relative error 2^-16), and whose right operand is the bf16 offset itself.
 //
-// Block tile 128 (m) x 128 (n), K step 64, four wavefronts in a 2 x 2 arrangement, each owning a
-// 64 x 64 sub-tile as 2 x 2 v_mfma_f32_32x32x16_bf16 accumulators.
+// Block tile 256 (m) x 128 (n), K step 64, eight wavefronts in a 4 x 2 arrangement, each owning a
+// 64 x 64 sub-tile as 2 x 2 v_mfma_f32_32x32x16_bf16 accumulators.  Two LDS buffers: while the
+// matrix cores work on K step s, the activations and codes of step s+1 are already in registers
+// (loaded before the MFMAs were issued) and are looked up / written to the other buffer behind
+// them; one barrier per K step.
 #include "any4_device.h"
 #include "any4_internal.h"
+#include <type_traits>
 
 namespace any4 {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int PBM = 128, PBN = 128, PBK = 64;
+constexpr int PBM = 256, PBN = 128, PBK = 64;
+constexpr int PTHREADS = 512;
 constexpr int PLD = PBK + 8;          // LDS row stride in bf16 elements (144 B: keeps 16-byte reads spread over banks)
 
 // X[m][g] = sum of the 128 activations of group g, in fp32, stored as two bf16 (high part,
@@ -57,17 +62,20 @@ __global__ __launch_bounds__(256) void group_sums_kernel(const uint16_t* __restr
         for (int c = (int)(2 * G) + sub; c < KP; c += 16) xs[m * KP + c] = 0;
 }
 
+// LDS copy of the block's row tables, laid out so that the 32 lanes LDS serves together never share
+// a bank: a half-wavefront holds 8 rows x 4 quarter-threads, and entry c of (row, quarter) lives at
+// dword (row / 8) * (32 << BITS) + c * 32 + (row % 8) * 4 + quarter (every row is stored 4 times).
 template <int BITS>
-__global__ __launch_bounds__(256) void prefill_kernel(
+__global__ __launch_bounds__(PTHREADS, 1) void prefill_kernel(
     const uint16_t* __restrict__ x, const uint32_t* __restrict__ codes,
     const uint16_t* __restrict__ lut, const uint16_t* __restrict__ scale,
     const uint16_t* __restrict__ offset, const uint16_t* __restrict__ xsums, int KP,
     int64_t M, int64_t N, int64_t K, uint16_t* __restrict__ y) {
     constexpr int L = 1 << BITS;
-    constexpr uint32_t mask = L - 1;
-    __shared__ __attribute__((aligned(16))) uint16_t xs[PBM * PLD];
-    __shared__ __attribute__((aligned(16))) uint16_t ws[PBN * PLD];
-    __shared__ uint16_t table[PBN][L + 2];
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    uint16_t* xs = reinterpret_cast<uint16_t*>(smem);                              // [2][PBM][PLD]
+    uint16_t* ws = xs + 2 * PBM * PLD;                                             // [2][PBN][PLD]
+    uint32_t* table = reinterpret_cast<uint32_t*>(ws + 2 * PBN * PLD);             // [PBN / 8][L][32], bf16 value in the low half
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
@@ -75,116 +83,159 @@ __global__ __launch_bounds__(256) void prefill_kernel(
     const int64_t G = K / kGroup, RW = row_words(K, BITS);
 
     // per-row tables of this block's weight rows (rows past N are clamped: they are never stored)
-    for (int i = tid; i < PBN * L; i += 256) {
-        const int r = i / L, c = i % L;
-        table[r][c] = lut[min(n0 + r, N - 1) * L + c];
+    for (int i = tid; i < PBN * L * 4; i += PTHREADS) {
+        const int cp = i & 3, r = (i >> 2) & 7, c = (i >> 5) & (L - 1), blk = i >> (5 + BITS);
+        table[i] = lut[min(n0 + blk * 8 + r, N - 1) * L + c];
+        (void)cp;
     }
 
-    // weight slab: thread -> (row, 32-code half of the K step)
-    const int wrow = tid >> 1, whalf = tid & 1;
+    // weight slab: thread -> (row, 16-code quarter of the K step)
+    const int wrow = tid >> 2, wq = tid & 3;
     const int64_t wn_glob = min(n0 + wrow, N - 1);
-    const uint32_t* wsrc = codes + wn_glob * RW;
-    // the two output columns this lane owns (one per 32-wide n tile of its wavefront)
-    int64_t ncol[2];
+    // word offset / bit shift of the thread's 16 codes inside the K step's (2 * BITS)-word chunk
+    const int qword = BITS == 4 ? 2 * wq : (BITS == 2 ? wq : (6 * wq) >> 2);
+    const int qshift = BITS == 3 ? ((6 * wq) & 3) * 8 : 0;
+    const uint32_t* wsrc = codes + wn_glob * RW + qword;
+    // LDS byte address of this thread's entry 0 (the kernel has no static LDS: dynamic LDS starts at 0)
+    const uint32_t tbase = (uint32_t)((2 * PBM * PLD + 2 * PBN * PLD) * 2 + ((wrow >> 3) * (32 << BITS) + (wrow & 7) * 4 + wq) * 4);
+    typedef const __attribute__((address_space(3))) uint32_t* lds_u32;
+    // activation slab: thread -> 4 rows (256 rows / 64), one 16-byte column piece
+    const int xr_row = tid >> 3, xc8 = tid & 7;
+    int64_t xm[4];                                                          // rows past M are clamped, never stored
 #pragma unroll
-    for (int j = 0; j < 2; ++j) ncol[j] = min(n0 + wn * 64 + j * 32 + (lane & 31), N - 1);
+    for (int pi = 0; pi < 4; ++pi) xm[pi] = min(m0 + pi * 64 + xr_row, M - 1);
+    // the two output columns this lane owns (one per 32-wide n tile of its wavefront)
+    const uint16_t* scol[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) scol[j] = scale + min(n0 + wn * 64 + j * 32 + (lane & 31), N - 1) * G;
 
-    f32x16 acc[2][2];
+    f32x16 acc[2][2], part[2][2];
+    f32x16 zero;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) zero[v] = 0.f;
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+        for (int j = 0; j < 2; ++j) { acc[i][j] = zero; part[i][j] = zero; }
 
-    const int64_t main_steps = K / PBK, tail_steps = (KP + PBK - 1) / PBK;
-    for (int64_t step = 0; step < main_steps + tail_steps; ++step) {
-        const bool tail = step >= main_steps;            // block-uniform
-        const int64_t k0 = (tail ? step - main_steps : step) * PBK;
-        // ---- global loads into registers
-        uint4 xr[4];
+    // ---- registers of the K step being fetched
+    uint4 xr[4];
+    uint32_t qw[2];
+    auto fetch_main = [&](int64_t k0) {
 #pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            const int idx = p * 256 + tid, r = idx >> 3, c8 = idx & 7;
-            const int64_t m = m0 + r, c = k0 + c8 * 8;
-            xr[p] = make_uint4(0, 0, 0, 0);
-            if (m < M) {
-                if (!tail) xr[p] = *reinterpret_cast<const uint4*>(x + m * K + c);
-                else if (c < KP) xr[p] = *reinterpret_cast<const uint4*>(xsums + m * KP + c);
-            }
+        for (int pi = 0; pi < 4; ++pi) xr[pi] = *reinterpret_cast<const uint4*>(x + xm[pi] * K + xc8 * 8 + k0);
+        const int64_t wbase = (k0 >> 5) * BITS;              // the K step's codes start at word (k0 / 32) * BITS
+        qw[0] = wsrc[wbase];
+        qw[1] = BITS == 2 ? 0u : wsrc[wbase + 1];
+    };
+    auto stage_x = [&](int buf) {
+        uint16_t* xb = xs + buf * PBM * PLD;
+#pragma unroll
+        for (int pi = 0; pi < 4; ++pi)
+            *reinterpret_cast<uint4*>(&xb[(pi * 64 + xr_row) * PLD + xc8 * 8]) = xr[pi];
+    };
+    // code j (0..15) of the fetched quarter
+    auto code_of = [&](uint32_t lo, uint32_t hi, int j) -> uint32_t {
+        if constexpr (BITS == 4) return __builtin_amdgcn_ubfe(j < 8 ? lo : hi, 4 * (j & 7), 4);
+        else if constexpr (BITS == 2) return __builtin_amdgcn_ubfe(lo, 2 * j, 2);
+        else {
+            const int bit = 3 * j;
+            if (bit + 3 <= 32) return __builtin_amdgcn_ubfe(lo, bit, 3);
+            if (bit >= 32) return __builtin_amdgcn_ubfe(hi, bit - 32, 3);
+            return __builtin_amdgcn_alignbit(hi, lo, bit) & 7u;
         }
-        uint32_t q[BITS];
-        float sc[2] = {1.f, 1.f};
-        if (!tail) {
-            const int64_t wbase = ((k0 >> 5) + whalf) * BITS;  // word offset of this thread's 32 codes
-#pragma unroll
-            for (int i = 0; i < BITS; ++i) q[i] = wsrc[wbase + i];
-#pragma unroll
-            for (int j = 0; j < 2; ++j) sc[j] = bf16_to_f32(scale[ncol[j] * G + k0 / kGroup]);
-        }
-
-        __syncthreads();                                       // previous step's MFMA reads are done (and the tables are written)
-        // ---- stage into LDS
-#pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            const int idx = p * 256 + tid, r = idx >> 3, c8 = idx & 7;
-            *reinterpret_cast<uint4*>(&xs[r * PLD + c8 * 8]) = xr[p];
+    };
+    auto stage_w_main = [&](int buf) {
+        uint16_t* wb = ws + buf * PBN * PLD;
+        uint32_t lo = qw[0], hi = qw[1];
+        if constexpr (BITS == 3) {
+            const unsigned long long v = (((unsigned long long)hi << 32) | lo) >> qshift;
+            lo = (uint32_t)v; hi = (uint32_t)(v >> 32);
         }
 #pragma unroll
-        for (int r8 = 0; r8 < 4; ++r8) {
-            uint32_t pk[4];
-            if (!tail) {
+        for (int hlf = 0; hlf < 2; ++hlf) {
+            uint32_t b[8];
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const int bit = (r8 * 8 + j) * BITS;
-                    uint32_t c = q[bit >> 5] >> (bit & 31);
-                    if ((bit & 31) + BITS > 32) c |= q[(bit >> 5) + 1] << (32 - (bit & 31));
-                    const uint32_t b = table[wrow][c & mask];
-                    if (j & 1) pk[j >> 1] |= b << 16; else pk[j >> 1] = b;
-                }
-            } else {
-                // columns c, c+1 of the group dimension both carry offset[n][c/2]
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int64_t g = (k0 + whalf * 32 + r8 * 8 + 2 * j) >> 1;
-                    const uint32_t b = g < G ? offset[wn_glob * G + g] : 0u;
-                    pk[j] = b | (b << 16);
-                }
-            }
-            *reinterpret_cast<uint4*>(&ws[wrow * PLD + whalf * 32 + r8 * 8]) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+            for (int j = 0; j < 8; ++j) b[j] = *reinterpret_cast<lds_u32>(tbase + (code_of(lo, hi, hlf * 8 + j) << 7));
+            *reinterpret_cast<uint4*>(&wb[wrow * PLD + wq * 16 + hlf * 8]) =
+                make_uint4(b[0] | (b[1] << 16), b[2] | (b[3] << 16), b[4] | (b[5] << 16), b[6] | (b[7] << 16));
         }
-        __syncthreads();
-        // ---- matrix cores: partial products of this K step, then one fp32 scale per column
-        f32x16 part[2][2];
+    };
+    // matrix cores on buffer `buf`; FIRST: the K step starts a group, its first MFMAs take a zero accumulator
+    auto mma = [&](int buf, auto first) {
+        constexpr bool FIRST = decltype(first)::value;
+        const uint16_t* xb = xs + buf * PBM * PLD;
+        const uint16_t* wb = ws + buf * PBN * PLD;
 #pragma unroll
         for (int kk = 0; kk < PBK / 16; ++kk) {
             const int col = kk * 16 + (lane >> 5) * 8;
             bf16x8 a[2], b[2];
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
-                a[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&xs[(wm * 64 + i * 32 + (lane & 31)) * PLD + col]));
-                b[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&ws[(wn * 64 + i * 32 + (lane & 31)) * PLD + col]));
+                a[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&xb[(wm * 64 + i * 32 + (lane & 31)) * PLD + col]));
+                b[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&wb[(wn * 64 + i * 32 + (lane & 31)) * PLD + col]));
             }
 #pragma unroll
             for (int i = 0; i < 2; ++i)
 #pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    if (kk == 0) {
-                        f32x16 zero;
-#pragma unroll
-                        for (int v = 0; v < 16; ++v) zero[v] = 0.f;
-                        part[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], zero, 0, 0, 0);
-                    } else {
-                        part[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], part[i][j], 0, 0, 0);
-                    }
-                }
+                for (int j = 0; j < 2; ++j)
+                    part[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], (FIRST && kk == 0) ? zero : part[i][j], 0, 0, 0);
         }
+    };
+    auto fold = [&](float s0, float s1) {
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
+            for (int v = 0; v < 16; ++v) {
+                acc[i][0][v] = __builtin_fmaf(part[i][0][v], s0, acc[i][0][v]);
+                acc[i][1][v] = __builtin_fmaf(part[i][1][v], s1, acc[i][1][v]);
+            }
+    };
+    using T = std::true_type;
+    using F = std::false_type;
+
+    // ---- main loop over groups of 128 (two K steps each).  While the matrix cores work on one buffer,
+    //      the next K step (fetched before the MFMAs were issued) is looked up and written to the other.
+    fetch_main(0);
+    __syncthreads();                                           // tables are written
+    stage_x(0);
+    stage_w_main(0);
+    __syncthreads();
+    for (int64_t g = 0; g < G; ++g) {
+        const float s0 = bf16_to_f32(scol[0][g]), s1 = bf16_to_f32(scol[1][g]);
+        const bool more = g + 1 < G;
+        fetch_main(g * kGroup + PBK);
+        mma(0, T{});
+        stage_x(1);
+        stage_w_main(1);
+        __syncthreads();
+        if (more) fetch_main((g + 1) * kGroup);
+        mma(1, F{});
+        if (more) { stage_x(0); stage_w_main(0); }
+        fold(s0, s1);
+        __syncthreads();
+    }
+
+    // ---- offset term: a few more K steps over the group dimension (activation group sums split into
+    //      bf16 hi + lo in columns 2g, 2g+1; both columns meet offset[n][g]); unscaled
+    for (int64_t k0 = 0; k0 < KP; k0 += PBK) {
 #pragma unroll
-                for (int v = 0; v < 16; ++v) acc[i][j][v] = __builtin_fmaf(part[i][j][v], sc[j], acc[i][j][v]);
+        for (int pi = 0; pi < 4; ++pi)
+            xr[pi] = k0 + xc8 * 8 < KP ? *reinterpret_cast<const uint4*>(xsums + xm[pi] * KP + xc8 * 8 + k0) : make_uint4(0, 0, 0, 0);
+        uint32_t pk[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int64_t gg = (k0 + wq * 16 + 2 * j) >> 1;
+            const uint32_t b = gg < G ? offset[wn_glob * G + gg] : 0u;
+            pk[j] = b | (b << 16);
+        }
+        stage_x(0);
+        *reinterpret_cast<uint4*>(&ws[wrow * PLD + wq * 16]) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+        *reinterpret_cast<uint4*>(&ws[wrow * PLD + wq * 16 + 8]) = make_uint4(pk[4], pk[5], pk[6], pk[7]);
+        __syncthreads();
+        mma(0, T{});
+        fold(1.f, 1.f);
+        __syncthreads();
     }
 
     // ---- store: accumulator element v of a lane is row 8*(v/4) + 4*(lane/32) + v%4, column lane%32
@@ -199,6 +250,10 @@ __global__ __launch_bounds__(256) void prefill_kernel(
                 if (m < M && n < N) y[m * N + n] = (uint16_t)f32_to_bf16(acc[i][j][v]);
             }
         }
+}
+
+constexpr size_t prefill_lds_bytes(int bits) {
+    return (size_t)(2 * PBM * PLD + 2 * PBN * PLD) * 2 + (size_t)PBN * (1 << bits) * 4 * 4;
 }
 
 size_t prefill_workspace_bytes(int64_t M, int64_t K) {
@@ -218,12 +273,21 @@ hipError_t launch_prefill(const uint16_t* x, const uint32_t* codes, const uint16
     hipLaunchKernelGGL(group_sums_kernel, dim3((unsigned)sblocks), dim3(256), 0, stream, x, M, K, KP, xsums);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const dim3 grid((unsigned)gm, (unsigned)gn), block(256);
+    const dim3 grid((unsigned)gm, (unsigned)gn), block(PTHREADS);
+#define ANY4_PREFILL(B)                                                                                           \
+    do {                                                                                                          \
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(prefill_kernel<B>),                                 \
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)prefill_lds_bytes(B));           \
+        if (e != hipSuccess) return e;                                                                            \
+        hipLaunchKernelGGL(prefill_kernel<B>, grid, block, prefill_lds_bytes(B), stream, x, codes, lut, scale,    \
+                           offset, xsums, KP, M, N, K, y);                                                        \
+    } while (0)
     switch (bits) {
-        case 4: hipLaunchKernelGGL(prefill_kernel<4>, grid, block, 0, stream, x, codes, lut, scale, offset, xsums, KP, M, N, K, y); break;
-        case 3: hipLaunchKernelGGL(prefill_kernel<3>, grid, block, 0, stream, x, codes, lut, scale, offset, xsums, KP, M, N, K, y); break;
-        default: hipLaunchKernelGGL(prefill_kernel<2>, grid, block, 0, stream, x, codes, lut, scale, offset, xsums, KP, M, N, K, y); break;
+        case 4: ANY4_PREFILL(4); break;
+        case 3: ANY4_PREFILL(3); break;
+        default: ANY4_PREFILL(2); break;
     }
+#undef ANY4_PREFILL
     return hipGetLastError();
 }
 
