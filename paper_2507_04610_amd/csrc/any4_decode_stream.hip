@@ -162,8 +162,13 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
     unsigned char* const aux = smem + aux_base(BITS);                   // [kAuxDist] slots
     int* lastlist = reinterpret_cast<int*>(smem + list_base(BITS));     // [0] = count
 #ifdef ANY4_STAMPS
+    const long long stamp_entry = wall_clock64();
     long long* stamps = reinterpret_cast<long long*>(smem + lds_bytes(BITS));
     for (int i = threadIdx.x; i < WAVES * kStampSteps * 4; i += WAVES * 64) stamps[i] = 0;
+    __syncthreads();
+#define ST_MARK(i) do { if ((threadIdx.x & 63) == 0) stamps[(((threadIdx.x >> 6) * kStampSteps) + kStampSteps - 1) * 4 + (i)] = wall_clock64(); } while (0)
+#else
+#define ST_MARK(i) do {} while (0)
 #endif
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -380,6 +385,10 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
             for (int j = 0; j < 4; ++j)
                 xa[gi][j] = *reinterpret_cast<const uint4*>(xrow + (int64_t)group_of(gi) * kGroup + j * 8);
     }
+#if defined(ANY4_STAMPS) && defined(ANY4_PROBE)
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if (lane == 0) stamps[((w * kStampSteps) + kStampSteps - 2) * 4 + 0] = wall_clock64();
+#endif
     LutSrc lut0;
     if constexpr (AUX) {
         load_lut(lut0, t0);                              // the first tile's table comes straight from memory
@@ -408,6 +417,10 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
             for (int j = 0; j < 4; ++j)
                 if (!(live_row && gi < ngw)) xa[gi][j] = make_uint4(0, 0, 0, 0);
     }
+#if defined(ANY4_STAMPS) && defined(ANY4_PROBE)
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if (lane == 0) stamps[((w * kStampSteps) + kStampSteps - 2) * 4 + 1] = wall_clock64();
+#endif
     if constexpr (AUX) {
         build_table(lut0, 0);
         if (w < kAuxDist && w < ntiles) aux_write(w);
@@ -432,8 +445,16 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
         xo = make_uint4(hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16), lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16));
         if (q) xo = make_uint4(0, 0, 0, 0);
     }
+#if defined(ANY4_STAMPS) && defined(ANY4_PROBE)
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    if (lane == 0) stamps[((w * kStampSteps) + kStampSteps - 2) * 4 + 2] = wall_clock64();
+#endif
     if (tid == 0) lastlist[0] = 0;
     lds_barrier();
+#ifdef ANY4_STAMPS
+    if (lane == 0) stamps[((w * kStampSteps) + kStampSteps - 1) * 4 + 0] = stamp_entry;
+#endif
+    ST_MARK(1);
 
     const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
     // the tables are the first thing in the block's LDS (the kernel has no static LDS), so a table
@@ -588,11 +609,14 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
         }
     }
     reduce_store(t1 - 1);
+    ST_MARK(2);
 #ifdef ANY4_STAMPS
     lds_barrier();
     if (g_any4_dbg_stream)
-        for (int i = threadIdx.x; i < WAVES * kStampSteps * 4; i += WAVES * 64)
+        for (int i = threadIdx.x; i < WAVES * kStampSteps * 4; i += WAVES * 64) {
+            if ((i & 3) == 3 && ((i >> 2) % kStampSteps) == kStampSteps - 1) continue;     // written at the very end
             g_any4_dbg_stream[(int64_t)blockIdx.x * (16 * kStampSteps * 4) + i] = stamps[i];
+        }
 #endif
 
     // ---- more than one slab: arrive at the counters of all tiles of this block, then finish the
@@ -626,6 +650,11 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
             lds_barrier();
         }
     }
+#ifdef ANY4_STAMPS
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if (lane == 0 && g_any4_dbg_stream)
+        g_any4_dbg_stream[(int64_t)blockIdx.x * (16 * kStampSteps * 4) + ((w * kStampSteps) + kStampSteps - 1) * 4 + 3] = wall_clock64();
+#endif
 }
 
 #ifdef ANY4_STAMPS
