@@ -111,3 +111,35 @@ def make_case_device(M: int, N: int, K: int, bits: int = 4, seed: int = 0, devic
         "offset": offset.to(torch.bfloat16),
         "x": x.to(torch.bfloat16),
     }
+
+
+@dataclass
+class QuantCase:
+    """One quantiser problem on the host: a weight matrix, the mean absolute activation of
+    every input channel, and the uniform draws the k-means++ initialisation consumes."""
+    N: int
+    K: int
+    bits: int
+    seed: int
+    w: np.ndarray      # float32 [N, K]
+    act: np.ndarray    # float32 [K], > 0
+    u: np.ndarray      # float32 [N, 2^bits], each in [0, 1)
+
+
+def make_quant_case(N: int, K: int, bits: int = 4, seed: int = 0) -> QuantCase:
+    """Stand-in for one linear layer of a language model and its calibration statistics
+    (paper section 3.2, last paragraphs: weights of a linear module and the mean absolute
+    activation per channel from one calibration sample):
+      w    0.02 * Student-t(5): bell-shaped with heavy tails, float32 [N, K]
+      act  0.05 + 0.5 * |N(0, 1)| per input channel, every 97th channel 10x larger
+           (a few dominant channels), float32 [K]
+      u    uniform [0, 1) draws, float32 [N, 2^bits]
+    Draw order with numpy's PCG64 `default_rng(seed)`: w, act, u."""
+    if K % GROUP != 0:
+        raise ValueError("K must be a multiple of 128")
+    rng = np.random.default_rng(seed)
+    w = (rng.standard_t(5, size=(N, K)) * 0.02).astype(np.float32)
+    act = (0.05 + 0.5 * np.abs(rng.standard_normal(K))).astype(np.float32)
+    act[::97] *= np.float32(10.0)
+    u = rng.random((N, 1 << bits), dtype=np.float32)
+    return QuantCase(N, K, bits, seed, w, act, u)
