@@ -95,6 +95,42 @@ int any4_gemm(const uint16_t* x, const uint32_t* codes, const uint16_t* lut,
 /* Bytes of workspace any4_gemm needs for this problem (0 for invalid arguments). */
 size_t any4_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int bits);
 
+/*
+ * any4_quantize - the step before the GEMM: learn the per-row tables (section 3.2 "any4
+ * Algorithm"; appendix, Algorithm 1).  For every row independently:
+ *   1. group-wise scaling of section 2.5.1 over groups of 128 weights along K,
+ *        asymmetric (symmetric = 0): alpha = (max - min) / (2^bits - 1),      beta = min
+ *        symmetric  (symmetric = 1): alpha = max|w| / (2^(bits-1) - 1),       beta = 0
+ *      alpha and beta are rounded to bf16 (what the GEMM will read) and then
+ *      w_S = (w - beta) / alpha in fp32; a constant group takes alpha = 1;
+ *   2. weighted one-dimensional k-means with 2^bits centres on the scaled row, sample weight
+ *      alpha * act[k] (scale of the weight's group times the mean absolute activation of its
+ *      input channel): k-means++ start (appendix "K-Means Initialization") driven by the
+ *      caller's uniform draws u, then the E-step (nearest centre) and the M-step (Eq. B: the
+ *      weighted mean of a cluster) alternate in fp64 until no code changes or `iters` centre
+ *      updates were made; a cluster without weight keeps its centre;
+ *   3. the centres, sorted ascending, become the row's table (bf16), the codes are the indices
+ *      of the nearest centres.
+ * The outputs feed any4_pack / any4_gemm unchanged: alpha * lut[code] + beta reconstructs w.
+ *   w          in   fp32 [N][K]
+ *   act        in   fp32 [K], >= 0, mean |activation| per input channel; NULL = all ones
+ *   u          in   fp32 [N][2^bits], each in [0, 1): draw q picks centre q of the row's start
+ *   iters      in   >= 0, upper bound on the centre updates per row
+ *   codes_u8   out  uint8 [N][K], one code per byte (the input format of any4_pack)
+ *   lut        out  bf16 [N][2^bits], ascending
+ *   scale      out  bf16 [N][K/128]
+ *   offset     out  bf16 [N][K/128]
+ *   msteps     out  int32 [N], centre updates actually made per row; may be NULL
+ * K must not exceed any4_quantize_max_k() (a row is kept in on-chip memory); larger K returns
+ * ANY4_ERR_SHAPE.  Needs no workspace.
+ */
+int any4_quantize(const float* w, const float* act, const float* u, int64_t N, int64_t K,
+                  int bits, int symmetric, int iters, uint8_t* codes_u8, uint16_t* lut,
+                  uint16_t* scale, uint16_t* offset, int32_t* msteps, void* stream);
+
+/* Largest K any4_quantize accepts. */
+int64_t any4_quantize_max_k(void);
+
 /* Static, human-readable text for a return code. */
 const char* any4_strerror(int code);
 

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_PKG, "libany4.so")
 GROUP = 128
 
 EXPORTS = ("any4_pack", "any4_dequant", "any4_gemm", "any4_gemm_workspace_bytes",
-           "any4_strerror", "any4_version")
+           "any4_quantize", "any4_quantize_max_k", "any4_strerror", "any4_version")
 
 
 class Any4Error(RuntimeError):
@@ -45,6 +45,10 @@ def load_library() -> ctypes.CDLL:
     lib.any4_gemm.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, ci, vp, vp, ctypes.c_size_t, vp]
     lib.any4_gemm_workspace_bytes.restype = ctypes.c_size_t
     lib.any4_gemm_workspace_bytes.argtypes = [i64, i64, i64, ci]
+    lib.any4_quantize.restype = ci
+    lib.any4_quantize.argtypes = [vp, vp, vp, i64, i64, ci, ci, ci, vp, vp, vp, vp, vp, vp]
+    lib.any4_quantize_max_k.restype = i64
+    lib.any4_quantize_max_k.argtypes = []
     lib.any4_strerror.restype = ctypes.c_char_p
     lib.any4_strerror.argtypes = [ci]
     lib.any4_version.restype = ci
@@ -139,3 +143,31 @@ def any4_gemm(x: torch.Tensor, codes: torch.Tensor, lut: torch.Tensor, scale: to
     wbytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     _check(lib.any4_gemm(px, pc, pl, ps, po, M, N, K, bits, py, pw, wbytes, _stream()), "any4_gemm")
     return out
+
+
+def any4_quantize_max_k() -> int:
+    return int(load_library().any4_quantize_max_k())
+
+
+def any4_quantize(w: torch.Tensor, act: torch.Tensor | None, u: torch.Tensor, bits: int = 4,
+                  symmetric: bool = False, iters: int = 20):
+    """fp32 [N,K] weights, fp32 [K] mean |activation| per channel (or None), fp32 [N, 2^bits]
+    uniform draws -> dict with codes_u8 uint8 [N,K], lut bf16 [N,2^bits], scale / offset bf16
+    [N,K/128] and msteps int32 [N].  Everything stays in device memory."""
+    lib = load_library()
+    N, K = w.shape
+    L = 1 << bits
+    pw = _dev(w, torch.float32, "w")
+    pa = _dev(act, torch.float32, "act") if act is not None else None
+    if tuple(u.shape) != (N, L):
+        raise Any4Error(f"u must have shape ({N}, {L})")
+    pu = _dev(u, torch.float32, "u")
+    dev = w.device
+    codes = torch.empty((N, K), dtype=torch.uint8, device=dev)
+    lut = torch.empty((N, L), dtype=torch.bfloat16, device=dev)
+    scale = torch.empty((N, max(K // GROUP, 0)), dtype=torch.bfloat16, device=dev)
+    offset = torch.empty((N, max(K // GROUP, 0)), dtype=torch.bfloat16, device=dev)
+    msteps = torch.empty((N,), dtype=torch.int32, device=dev)
+    _check(lib.any4_quantize(pw, pa, pu, N, K, bits, int(symmetric), iters, codes.data_ptr(), lut.data_ptr(),
+                             scale.data_ptr(), offset.data_ptr(), msteps.data_ptr(), _stream()), "any4_quantize")
+    return {"codes_u8": codes, "lut": lut, "scale": scale, "offset": offset, "msteps": msteps}

@@ -54,4 +54,10 @@ hipError_t launch_prefill(const uint16_t* x, const uint32_t* codes, const uint16
 inline int prefill_kp(int64_t K) { return (int)((2 * (K / 128) + 15) / 16 * 16); }
 size_t prefill_workspace_bytes(int64_t M, int64_t K);
 
+// Quantiser: one block per row, the row lives in LDS, which bounds K.
+size_t quantize_max_k();
+hipError_t launch_quantize(const float* w, const float* act, const float* u, int64_t N, int64_t K, int bits,
+                           int symmetric, int iters, uint8_t* codes, uint16_t* lut, uint16_t* scale,
+                           uint16_t* offset, int32_t* msteps, hipStream_t stream);
+
 }  // namespace any4

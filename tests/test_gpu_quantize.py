@@ -1,0 +1,132 @@
+"""Parity of the HIP quantiser against its CPU oracle, through the C ABI, on a real MI355X.
+
+Bar: codes, tables, scales, offsets and the number of centre updates bit-exact.  Both sides
+take every decision (nearest centre, drawn sample) in fp64 on the same fp32 inputs; the only
+arithmetic that may differ is the association of fp64 sums (partial sums per thread), which can
+change a decision only when a value lies within ~1e-13 (relative) of a decision boundary.
+"""
+import numpy as np
+import pytest
+
+from paper_2507_04610_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def any4():
+    if not torch.cuda.is_available():
+        pytest.fail("no GPU visible: the parity tests must run on the GPU box")
+    import paper_2507_04610_amd as lib
+    lib.load_library()
+    return lib
+
+
+@pytest.fixture(scope="module")
+def qoracle():
+    from oracle import any4_quant_oracle
+    any4_quant_oracle.build()
+    return any4_quant_oracle
+
+
+def bits16(t):
+    return t.view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def run_and_compare(any4, qoracle, w, act, u, bits, symmetric, iters, what):
+    ref = qoracle.quantize(w, act, u, bits, symmetric=symmetric, iters=iters, threads=8)
+    got = any4.any4_quantize(torch.from_numpy(w).cuda(), None if act is None else torch.from_numpy(act).cuda(),
+                             torch.from_numpy(u).cuda(), bits, symmetric=symmetric, iters=iters)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits16(got["scale"]), ref["scale"]), (what, "scale")
+    assert np.array_equal(bits16(got["offset"]), ref["offset"]), (what, "offset")
+    assert np.array_equal(got["msteps"].cpu().numpy(), ref["msteps"]), (what, "msteps")
+    assert np.array_equal(bits16(got["lut"]), ref["lut"]), (what, "lut")
+    codes = got["codes_u8"].cpu().numpy()
+    bad = np.argwhere(codes != ref["codes_u8"])
+    assert bad.size == 0, (what, "codes", bad[:5].tolist(), len(bad))
+    return got, ref
+
+
+@pytest.mark.parametrize("bits", (4, 3, 2))
+@pytest.mark.parametrize("N,K", [(3, 128), (5, 384), (17, 1152), (64, 4096)])
+def test_quantize_matches_oracle(any4, qoracle, bits, N, K):
+    qc = inputs.make_quant_case(N, K, bits, seed=40 + bits)
+    run_and_compare(any4, qoracle, qc.w, qc.act, qc.u, bits, False, 25, (bits, N, K))
+
+
+@pytest.mark.parametrize("bits", (4, 3, 2))
+def test_quantize_symmetric_and_unit_activations(any4, qoracle, bits):
+    qc = inputs.make_quant_case(9, 1024, bits, seed=7)
+    run_and_compare(any4, qoracle, qc.w, qc.act, qc.u, bits, True, 25, ("symmetric", bits))
+    run_and_compare(any4, qoracle, qc.w, None, qc.u, bits, False, 25, ("act=None", bits))
+
+
+@pytest.mark.parametrize("iters", (0, 1, 3, 200))
+def test_quantize_iteration_caps(any4, qoracle, iters):
+    qc = inputs.make_quant_case(6, 768, 4, seed=3)
+    got, ref = run_and_compare(any4, qoracle, qc.w, qc.act, qc.u, 4, False, iters, ("iters", iters))
+    assert ref["msteps"].max() <= iters
+
+
+def test_quantize_long_rows(any4, qoracle):
+    """The Llama-3 down projections' K, and the largest K the library accepts."""
+    for K in (14336, any4.any4_quantize_max_k()):
+        qc = inputs.make_quant_case(4, K, 4, seed=K)
+        run_and_compare(any4, qoracle, qc.w, qc.act, qc.u, 4, False, 15, ("K", K))
+
+
+def test_quantize_degenerate_rows(any4, qoracle):
+    """Constant groups (alpha falls back to 1), a constant row (no sampling mass after the first
+    centre), a row with fewer distinct values than centres, channels with zero activation."""
+    qc = inputs.make_quant_case(6, 512, 4, seed=12)
+    w = qc.w.copy()
+    w[0, 128:256] = 0.25                                   # one constant group
+    w[1, :] = -0.5                                         # constant row
+    w[2, :] = np.tile(np.array([-1.0, -0.25, 0.5, 0.875], np.float32), 128)   # 4 distinct values
+    act = qc.act.copy()
+    act[::3] = 0.0
+    got, ref = run_and_compare(any4, qoracle, w, act, qc.u, 4, False, 20, "degenerate")
+    lut = inputs.bf16_bits_to_f32(ref["lut"])
+    sc = inputs.bf16_bits_to_f32(ref["scale"]).repeat(128, axis=1)
+    of = inputs.bf16_bits_to_f32(ref["offset"]).repeat(128, axis=1)
+    rec = np.take_along_axis(lut, ref["codes_u8"].astype(np.int64), axis=1) * sc + of
+    assert np.array_equal(rec[1], w[1]) and np.array_equal(rec[2], w[2])
+
+
+def test_quantize_feeds_the_gemm(any4, qoracle, oracle):
+    """quantize -> pack -> GEMM on the device against the oracle chain on the host, and the
+    quantised product stays close to the full-precision one."""
+    N, K, M, bits = 96, 1024, 4, 4
+    qc = inputs.make_quant_case(N, K, bits, seed=5)
+    got, ref = run_and_compare(any4, qoracle, qc.w, qc.act, qc.u, bits, False, 25, "chain")
+    rng = np.random.default_rng(9)
+    x = inputs.f32_to_bf16_bits((rng.standard_normal((M, K)) * qc.act[None, :]).astype(np.float32))
+    xd = torch.from_numpy(x.view(np.int16)).cuda().view(torch.bfloat16)
+    packed = any4.any4_pack(got["codes_u8"], bits)
+    y = any4.any4_gemm(xd, packed, got["lut"], got["scale"], got["offset"], bits)
+    y64 = oracle.gemm(x, oracle.pack(ref["codes_u8"], bits), ref["lut"], ref["scale"], ref["offset"], K, bits)
+    yf = inputs.bf16_bits_to_f32(bits16(y)).astype(np.float64)
+    tol = 1e-2 * oracle.rms(y64) + np.abs(y64) * 2.0 ** -8
+    assert np.all(np.abs(yf - y64) <= tol)
+    exact = inputs.bf16_bits_to_f32(x).astype(np.float64) @ qc.w.astype(np.float64).T
+    assert np.linalg.norm(y64 - exact) / np.linalg.norm(exact) < 0.2
+
+
+def test_quantize_rejects_bad_arguments(any4):
+    from paper_2507_04610_amd import binding
+    lib = any4.load_library()
+    kmax = any4.any4_quantize_max_k()
+    w = torch.zeros((1, kmax + 128), dtype=torch.float32, device="cuda")
+    u = torch.zeros((1, 16), dtype=torch.float32, device="cuda")
+    with pytest.raises(binding.Any4Error):
+        any4.any4_quantize(w, None, u, 4)
+    with pytest.raises(binding.Any4Error):
+        any4.any4_quantize(w[:, :256].contiguous(), None, u, 5)
+    out = torch.zeros(64, dtype=torch.uint8, device="cuda")
+    assert lib.any4_quantize(None, None, u.data_ptr(), 1, 128, 4, 0, 1, out.data_ptr(), out.data_ptr(),
+                             out.data_ptr(), out.data_ptr(), None, None) == -1
+    assert lib.any4_quantize(w.data_ptr(), None, u.data_ptr(), 1, 128, 4, 0, -1, out.data_ptr(), out.data_ptr(),
+                             out.data_ptr(), out.data_ptr(), None, None) == -2
