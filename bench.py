@@ -182,6 +182,41 @@ def main():
 
     if args.extras:
         del graph
+        # what the same launches cost when they only read the packed codes (94 % of the algorithmic
+        # bytes) and do no arithmetic: same rotation over layers, same graph replay, a plain read kernel
+        sink = torch.zeros(4, dtype=torch.int32, device=dev)
+        for g in layers[0]:
+            any4.any4_stream_read(g["codes"], sink)
+        torch.cuda.synchronize()
+        rgraph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(rgraph):
+            for s_ in range(args.steps):
+                for g in layers[s_ % args.layers]:
+                    any4.any4_stream_read(g["codes"], sink)
+        rgraph.replay()
+        torch.cuda.synchronize()
+        r0, r1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        r0.record()
+        rgraph.replay()
+        r1.record()
+        torch.cuda.synchronize()
+        read_ms = r0.elapsed_time(r1) / args.steps
+        code_bytes = sum(g["codes"].numel() * 4 for g in layers[0])
+        bigbuf = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        any4.any4_stream_read(bigbuf, sink)
+        torch.cuda.synchronize()
+        b0, b1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        b0.record()
+        any4.any4_stream_read(bigbuf, sink)
+        b1.record()
+        torch.cuda.synchronize()
+        extras["read_only_launches"] = {
+            "what": "the step's four launches replaced by a kernel that only reads each linear's packed codes",
+            "ms_per_step": read_ms, "code_bytes_per_step": code_bytes,
+            "GBps": code_bytes / (read_ms * 1e-3) / 1e9,
+            "gemm_step_over_read_step": ms_per_step / read_ms,
+            "one_GiB_read_GBps": (1 << 30) / (b0.elapsed_time(b1) * 1e-3) / 1e9}
+        del rgraph, bigbuf
         m8 = {}
         for gi, g in enumerate(layers[0]):
             rot = []
@@ -248,6 +283,41 @@ def main():
                     del rot
                     torch.cuda.empty_cache()
         extras["llama3_70b_any3_any2"] = low
+        # the quantiser that produces the GEMM's inputs: Llama-3-8B linears, any4, 20 centre updates
+        # at most; fp64 vector-ALU bound.  Flops counted: 2 per (sample, centre) distance, 3 per
+        # sample for the weighted sums, per pass; (2q + 1) per sample for start centre q.
+        qz = {}
+        for name, (N, K) in inputs.LLAMA3_8B_SHAPES.items():
+            t = inputs.make_quant_case_device(N, K, bits, seed=700, device=dev)
+            r = any4.any4_quantize(t["w"], t["act"], t["u"], bits, iters=20)
+            torch.cuda.synchronize()
+            ev = []
+            for _ in range(3):
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                r = any4.any4_quantize(t["w"], t["act"], t["u"], bits, iters=20)
+                b.record()
+                ev.append((a, b))
+            torch.cuda.synchronize()
+            ms = float(np.median([a.elapsed_time(b) for a, b in ev]))
+            passes = float(r["msteps"].float().mean().item()) + 1.0
+            L = 1 << bits
+            flops = N * K * (passes * (2 * L + 3) + L * L)
+            qz[name] = {"ms": ms, "rows_per_s": N / (ms * 1e-3), "Mweights_per_s": N * K / (ms * 1e-3) / 1e6,
+                        "mean_passes": passes, "fp64_TFLOPs": flops / (ms * 1e-3) / 1e12,
+                        "frac_of_fp64_vector_peak": flops / (ms * 1e-3) / 1e12 / 78.6}
+            del t, r
+            torch.cuda.empty_cache()
+        if args.cpu:
+            from oracle import any4_quant_oracle as qoracle
+            threads_q = min(16, os.cpu_count() or 1)
+            qc = inputs.make_quant_case(4 * threads_q, 4096, bits, seed=700)
+            t0 = time.perf_counter()
+            qoracle.quantize(qc.w, qc.act, qc.u, bits, iters=20, threads=threads_q)
+            dtq = time.perf_counter() - t0
+            qz["cpu_oracle"] = {"rows_per_s": qc.N / dtq, "cores": threads_q,
+                                "sample": f"{qc.N} rows of K = 4096, any4, 20 centre updates at most"}
+        extras["quantize_llama3_8b"] = qz
         layers = [layers_keep]
 
     # ------------------------------------------------------------------ CPU oracle beside it

@@ -131,6 +131,17 @@ int any4_quantize(const float* w, const float* act, const float* u, int64_t N, i
 /* Largest K any4_quantize accepts. */
 int64_t any4_quantize_max_k(void);
 
+/*
+ * any4_stream_read - measurement helper, not part of the method: reads the first
+ * (bytes / 16) * 16 bytes at p once with 16-byte loads and does nothing else.  The benchmark
+ * times it on the same buffers as the GEMM to report what a launch that only streams those
+ * bytes costs on the device.  The xor of all words read is written to sink[0] only if it equals
+ * `magic` (pass any value; the store exists so that the loads are kept).
+ *   p      in   device buffer, 16-byte aligned, at least 16 bytes
+ *   sink   out  uint32 [1], normally left untouched
+ */
+int any4_stream_read(const void* p, size_t bytes, uint32_t magic, uint32_t* sink, void* stream);
+
 /* Static, human-readable text for a return code. */
 const char* any4_strerror(int code);
 

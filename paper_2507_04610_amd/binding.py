@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_PKG, "libany4.so")
 GROUP = 128
 
 EXPORTS = ("any4_pack", "any4_dequant", "any4_gemm", "any4_gemm_workspace_bytes",
-           "any4_quantize", "any4_quantize_max_k", "any4_strerror", "any4_version")
+           "any4_quantize", "any4_quantize_max_k", "any4_stream_read", "any4_strerror", "any4_version")
 
 
 class Any4Error(RuntimeError):
@@ -49,6 +49,8 @@ def load_library() -> ctypes.CDLL:
     lib.any4_quantize.argtypes = [vp, vp, vp, i64, i64, ci, ci, ci, vp, vp, vp, vp, vp, vp]
     lib.any4_quantize_max_k.restype = i64
     lib.any4_quantize_max_k.argtypes = []
+    lib.any4_stream_read.restype = ci
+    lib.any4_stream_read.argtypes = [vp, ctypes.c_size_t, ctypes.c_uint32, vp, vp]
     lib.any4_strerror.restype = ctypes.c_char_p
     lib.any4_strerror.argtypes = [ci]
     lib.any4_version.restype = ci
@@ -171,3 +173,13 @@ def any4_quantize(w: torch.Tensor, act: torch.Tensor | None, u: torch.Tensor, bi
     _check(lib.any4_quantize(pw, pa, pu, N, K, bits, int(symmetric), iters, codes.data_ptr(), lut.data_ptr(),
                              scale.data_ptr(), offset.data_ptr(), msteps.data_ptr(), _stream()), "any4_quantize")
     return {"codes_u8": codes, "lut": lut, "scale": scale, "offset": offset, "msteps": msteps}
+
+
+def any4_stream_read(buf: torch.Tensor, sink: torch.Tensor, magic: int = 0x5EED1234) -> None:
+    """Measurement helper: read `buf` once on the current stream (see include/any4.h)."""
+    lib = load_library()
+    if not buf.is_cuda or not buf.is_contiguous():
+        raise Any4Error("buf must be a contiguous tensor in device memory")
+    ps = _dev(sink, torch.int32, "sink")
+    _check(lib.any4_stream_read(buf.data_ptr(), buf.numel() * buf.element_size(), magic, ps, _stream()),
+           "any4_stream_read")

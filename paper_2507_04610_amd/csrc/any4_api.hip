@@ -93,6 +93,14 @@ int any4_dequant(const uint32_t* codes, const uint16_t* lut, const uint16_t* sca
                ? ANY4_OK : ANY4_ERR_HIP;
 }
 
+int any4_stream_read(const void* p, size_t bytes, uint32_t magic, uint32_t* sink, void* stream) {
+    if (!p || !sink) return ANY4_ERR_NULL;
+    if (bytes < 16) return ANY4_ERR_SHAPE;
+    if (!aligned16(p)) return ANY4_ERR_ALIGN;
+    return launch_stream_read(p, bytes, magic, sink, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? ANY4_OK : ANY4_ERR_HIP;
+}
+
 int64_t any4_quantize_max_k(void) { return (int64_t)quantize_max_k(); }
 
 int any4_quantize(const float* w, const float* act, const float* u, int64_t N, int64_t K, int bits,

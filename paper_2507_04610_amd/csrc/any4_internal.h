@@ -54,6 +54,9 @@ hipError_t launch_prefill(const uint16_t* x, const uint32_t* codes, const uint16
 inline int prefill_kp(int64_t K) { return (int)((2 * (K / 128) + 15) / 16 * 16); }
 size_t prefill_workspace_bytes(int64_t M, int64_t K);
 
+// Read-only streaming kernel for the benchmark's "what does a launch that reads these bytes cost" figure.
+hipError_t launch_stream_read(const void* p, size_t bytes, uint32_t magic, uint32_t* sink, hipStream_t stream);
+
 // Quantiser: one block per row, the row lives in LDS, which bounds K.
 size_t quantize_max_k();
 hipError_t launch_quantize(const float* w, const float* act, const float* u, int64_t N, int64_t K, int bits,

@@ -143,3 +143,22 @@ def make_quant_case(N: int, K: int, bits: int = 4, seed: int = 0) -> QuantCase:
     act[::97] *= np.float32(10.0)
     u = rng.random((N, 1 << bits), dtype=np.float32)
     return QuantCase(N, K, bits, seed, w, act, u)
+
+
+def make_quant_case_device(N: int, K: int, bits: int = 4, seed: int = 0, device="cuda"):
+    """The quantiser recipe drawn with torch's generator directly in device memory (full-size
+    benchmark matrices): Student-t(5) = normal / sqrt(chi-square(5) / 5).  Returns a dict of
+    float32 tensors w [N,K], act [K], u [N, 2^bits]."""
+    import torch
+    g = torch.Generator(device=device)
+    g.manual_seed(seed)
+    z = torch.randn((N, K), dtype=torch.float32, device=device, generator=g)
+    chi = torch.zeros((N, K), dtype=torch.float32, device=device)
+    for _ in range(5):
+        chi += torch.randn((N, K), dtype=torch.float32, device=device, generator=g) ** 2
+    w = 0.02 * z / torch.sqrt(chi / 5.0)
+    del z, chi
+    act = 0.05 + 0.5 * torch.randn((K,), dtype=torch.float32, device=device, generator=g).abs()
+    act[::97] *= 10.0
+    u = torch.rand((N, 1 << bits), dtype=torch.float32, device=device, generator=g)
+    return {"w": w.contiguous(), "act": act.contiguous(), "u": u.contiguous()}
