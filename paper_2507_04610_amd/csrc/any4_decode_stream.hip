@@ -115,7 +115,15 @@ struct Params {
     int M, G;                        // G = K / 128
     int slabs, slab_groups;          // groups per slab (the last slab may have fewer)
     int blocks_per_slab, tiles;
+#ifdef ANY4_TUNING
+    int stop;                        // tuning builds: leave the kernel early at a numbered point
+#endif
 };
+#ifdef ANY4_TUNING
+#define ANY4_STOP(i) do { if (p.stop == (i)) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); return; } } while (0)
+#else
+#define ANY4_STOP(i) do {} while (0)
+#endif
 
 // LDS barrier that does not wait for outstanding global loads (the prefetched codes stay in flight)
 __device__ __forceinline__ void lds_barrier() {
@@ -175,6 +183,7 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 15, q = lane >> 4;
 
+    ANY4_STOP(1);
     const int slab = blockIdx.x / p.blocks_per_slab, bb = blockIdx.x - slab * p.blocks_per_slab;
     if (slab >= p.slabs) return;
     const int t0 = (int)((int64_t)bb * p.tiles / p.blocks_per_slab);
@@ -375,9 +384,24 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
     // ---- prologue.  Activations first (small, and the first thing the matrix cores need), then the
     //      codes of the ring and the small inputs.
     // activations of the wavefront's groups as A operands: lane (m = n, q), MFMA j of group gi holds
-    // x[m][(gw0 + gi) * 128 + q * 32 + j * 8 .. + 8]; rows m >= M and missing groups are zero
+    // x[m][(gw0 + gi) * 128 + q * 32 + j * 8 .. + 8]; rows m >= M and missing groups are zero.
+    // Up to kStageRows rows: the wavefront fetches each row's GW * 128 activations with ONE 16-byte
+    // load per lane and re-distributes them through LDS (the partial-sum buffer is idle until the
+    // first tile), instead of 4 * GW loads in which most lanes fetch what they will zero anyway.
+    constexpr int kStageRows = 2;
+    static_assert(kStageRows * GW * 256 * kWaves <= kRedBytes, "activation staging lives in the partial-sum buffer");
+    const bool compact = M <= kStageRows;                 // the same for every thread
     uint4 xa[GW][4];
-    {
+    uint4 xraw[kStageRows];
+    if (compact) {
+        const bool has = lane * 8 < ngw * kGroup;        // GW * 128 = up to 64 lanes x 8 elements
+#pragma unroll
+        for (int m = 0; m < kStageRows; ++m) {
+            xraw[m] = make_uint4(0, 0, 0, 0);
+            if (m < M && has)
+                xraw[m] = *reinterpret_cast<const uint4*>(p.x + (int64_t)m * K + (int64_t)gw0 * kGroup + lane * 8);
+        }
+    } else {
         const uint16_t* xrow = p.x + (int64_t)min(n, M - 1) * K + q * 32;
 #pragma unroll
         for (int gi = 0; gi < GW; ++gi)
@@ -385,10 +409,6 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
             for (int j = 0; j < 4; ++j)
                 xa[gi][j] = *reinterpret_cast<const uint4*>(xrow + (int64_t)group_of(gi) * kGroup + j * 8);
     }
-#if defined(ANY4_STAMPS) && defined(ANY4_PROBE)
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    if (lane == 0) stamps[((w * kStampSteps) + kStampSteps - 2) * 4 + 0] = wall_clock64();
-#endif
     LutSrc lut0;
     if constexpr (AUX) {
         load_lut(lut0, t0);                              // the first tile's table comes straight from memory
@@ -409,7 +429,26 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
             load_so(sraw[d], oraw[d], t);
         }
     }
-    {
+    ANY4_STOP(4);
+    if (compact) {
+        // row m of this wavefront at stage + m * (GW * 16) uint4; a lane's MFMA-j piece of group gi
+        // is uint4 number gi * 16 + q * 4 + j of its row
+        uint4* stage = reinterpret_cast<uint4*>(red) + w * (kStageRows * GW * 16);
+#pragma unroll
+        for (int m = 0; m < kStageRows; ++m)
+            if (m < M && lane < GW * 16) stage[m * (GW * 16) + lane] = xraw[m];
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");          // same wavefront wrote it: no barrier needed
+#pragma unroll
+        for (int gi = 0; gi < GW; ++gi)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) xa[gi][j] = make_uint4(0, 0, 0, 0);
+        if (n < M) {
+#pragma unroll
+            for (int gi = 0; gi < GW; ++gi)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) xa[gi][j] = stage[n * (GW * 16) + gi * 16 + q * 4 + j];
+        }
+    } else {
         const bool live_row = n < M;
 #pragma unroll
         for (int gi = 0; gi < GW; ++gi)
@@ -417,10 +456,36 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
             for (int j = 0; j < 4; ++j)
                 if (!(live_row && gi < ngw)) xa[gi][j] = make_uint4(0, 0, 0, 0);
     }
-#if defined(ANY4_STAMPS) && defined(ANY4_PROBE)
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    if (lane == 0) stamps[((w * kStampSteps) + kStampSteps - 2) * 4 + 1] = wall_clock64();
-#endif
+
+    // group sums of the activations -> A operand of the offset MFMA (q == 0 lanes: hi parts in
+    // k-slots 0..3, lo parts in k-slots 4..7; other lanes: zero); done as soon as the activations
+    // are there, while the codes are still on their way.  The matrix cores add them up: with an
+    // all-ones A operand and the activations as B operand, D[i][m] = sum_k x[m][k] for every i, and
+    // the lanes of column m (the lanes that hold row m of x) receive exactly their own row's sum.
+    uint4 xo;
+    {
+        const uint4 ones = make_uint4(0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u);
+        const f32x4 z4 = {0.f, 0.f, 0.f, 0.f};
+        f32x4 gs[GW];
+#pragma unroll
+        for (int gi = 0; gi < GW; ++gi) gs[gi] = z4;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int gi = 0; gi < GW; ++gi)
+                gs[gi] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ones),
+                                                                 __builtin_bit_cast(bf16x8, xa[gi][j]), gs[gi], 0, 0, 0);
+        uint32_t hi[4] = {0, 0, 0, 0}, lo[4] = {0, 0, 0, 0};
+#pragma unroll
+        for (int gi = 0; gi < GW; ++gi) {
+            const float sgi = gs[gi][0];
+            hi[gi] = f32_to_bf16(sgi);
+            lo[gi] = f32_to_bf16(sgi - bf16_to_f32(hi[gi]));
+        }
+        xo = make_uint4(hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16), lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16));
+        if (q) xo = make_uint4(0, 0, 0, 0);
+    }
+    ANY4_STOP(5);
     if constexpr (AUX) {
         build_table(lut0, 0);
         if (w < kAuxDist && w < ntiles) aux_write(w);
@@ -428,33 +493,14 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
         build_table(lut_ring[0], 0);
         load_lut(lut_ring[0], min(t0 + kDepth, t1 - 1));
     }
-
-    // group sums of the activations -> A operand of the offset MFMA (q == 0 lanes: hi parts in
-    // k-slots 0..3, lo parts in k-slots 4..7; other lanes: zero)
-    uint4 xo;
-    {
-        uint32_t hi[4] = {0, 0, 0, 0}, lo[4] = {0, 0, 0, 0};
-#pragma unroll
-        for (int gi = 0; gi < GW; ++gi) {
-            float s = (sum8(xa[gi][0]) + sum8(xa[gi][1])) + (sum8(xa[gi][2]) + sum8(xa[gi][3]));
-            s += __shfl_xor(s, 16);
-            s += __shfl_xor(s, 32);
-            hi[gi] = f32_to_bf16(s);
-            lo[gi] = f32_to_bf16(s - bf16_to_f32(hi[gi]));
-        }
-        xo = make_uint4(hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16), lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16));
-        if (q) xo = make_uint4(0, 0, 0, 0);
-    }
-#if defined(ANY4_STAMPS) && defined(ANY4_PROBE)
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    if (lane == 0) stamps[((w * kStampSteps) + kStampSteps - 2) * 4 + 2] = wall_clock64();
-#endif
+    ANY4_STOP(6);
     if (tid == 0) lastlist[0] = 0;
     lds_barrier();
 #ifdef ANY4_STAMPS
     if (lane == 0) stamps[((w * kStampSteps) + kStampSteps - 1) * 4 + 0] = stamp_entry;
 #endif
     ST_MARK(1);
+    ANY4_STOP(2);
 
     const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
     // the tables are the first thing in the block's LDS (the kernel has no static LDS), so a table
@@ -608,6 +654,7 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
             }
         }
     }
+    ANY4_STOP(3);
     reduce_store(t1 - 1);
     ST_MARK(2);
 #ifdef ANY4_STAMPS
@@ -753,6 +800,9 @@ hipError_t launch_decode_stream(const uint16_t* x, const uint32_t* codes, const 
     p.N = N; p.K = K; p.M = (int)M; p.G = (int)(K / kGroup);
     p.slabs = sp.slabs; p.slab_groups = sp.slab_groups; p.blocks_per_slab = sp.blocks_per_slab;
     p.tiles = (int)sp.tiles;
+#ifdef ANY4_TUNING
+    if (const char* e = getenv("ANY4_TUNE_STOP")) p.stop = atoi(e);
+#endif
     const int grid = sp.slabs * sp.blocks_per_slab;
     if (bits == 4) return launch_stream_b<4>(p, sp, grid, stream);
     if (bits == 3) return launch_stream_b<3>(p, sp, grid, stream);
