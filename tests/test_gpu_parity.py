@@ -148,6 +148,16 @@ def test_gemm_decode_slabs_and_ragged_groups(any4, oracle, bits, M, N, K):
     run_gemm_case(any4, oracle, M, N, K, bits, seed=inputs.case_seed(7, bits, M))
 
 
+@pytest.mark.parametrize("bits", (4, 3, 2))
+@pytest.mark.parametrize("M,N,K", [(1, 40, 8192), (2, 100, 14336), (1, 115, 28672), (2, 5000, 8192),
+                                   (1, 16, 5120), (2, 33, 28672), (1, 48, 12288)])
+def test_gemm_decode_long_k_few_rows(any4, oracle, bits, M, N, K):
+    """One or two activation rows (fetched once per wavefront and re-distributed through LDS) and K
+    beyond one slab: 2 to 7 slabs combined through the workspace, several tiles per block, ragged
+    last tile."""
+    run_gemm_case(any4, oracle, M, N, K, bits, seed=inputs.case_seed(9, bits, M))
+
+
 def test_gemm_zero_offset_and_unsorted_table(any4, oracle):
     def mutate(cs):
         cs.offset[:] = 0                                   # symmetric scaling: beta = 0
