@@ -318,6 +318,42 @@ def main():
             qz["cpu_oracle"] = {"rows_per_s": qc.N / dtq, "cores": threads_q,
                                 "sample": f"{qc.N} rows of K = 4096, any4, 20 centre updates at most"}
         extras["quantize_llama3_8b"] = qz
+        # the paper's own latency experiment (section 5, "Speed Comparisons": a 1 x K input times a K x K
+        # weight, K = 1K .. 16K): any4 GEMM against the bf16 GEMM of the vendor library that torch calls,
+        # weights rotated over enough copies to come from HBM
+        sq = {}
+
+        def graph_us(calls, reps=48):
+            """microseconds per call: `reps` calls (cycling through `calls`) captured in one graph"""
+            for c in calls[:2]:
+                c()
+            torch.cuda.synchronize()
+            gsq = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gsq):
+                for r_ in range(reps):
+                    calls[r_ % len(calls)]()
+            gsq.replay()
+            torch.cuda.synchronize()
+            a_, b_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a_.record()
+            gsq.replay()
+            b_.record()
+            torch.cuda.synchronize()
+            return a_.elapsed_time(b_) * 1e3 / reps
+
+        for Ks in (1024, 2048, 4096, 8192, 16384):
+            copies = max(2, min(16, int(1.2e9 // (Ks * Ks * 2)) + 1))
+            rot = [make_layer({"sq": (Ks, Ks)}, 1, seed=900 + c)[0] for c in range(copies)]
+            us = graph_us([(lambda g=g: launch(g)) for g in rot])
+            wb = [torch.randn((Ks, Ks), device=dev).to(torch.bfloat16) for _ in range(copies)]
+            xb = torch.randn((1, Ks), device=dev).to(torch.bfloat16)
+            yb = torch.empty((1, Ks), dtype=torch.bfloat16, device=dev)
+            us_bf16 = graph_us([(lambda wmat=wmat: torch.matmul(xb, wmat.t(), out=yb)) for wmat in wb])
+            sq[f"K{Ks}"] = {"any4_us": us, "bf16_library_us": us_bf16, "speedup_over_bf16": us_bf16 / us,
+                            "any4_GBps": algorithmic_bytes(1, Ks, Ks, bits) / (us * 1e-6) / 1e9}
+            del rot, wb
+            torch.cuda.empty_cache()
+        extras["square_1xK_KxK"] = sq
         layers = [layers_keep]
 
     # ------------------------------------------------------------------ CPU oracle beside it
