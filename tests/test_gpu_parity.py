@@ -168,6 +168,18 @@ def test_gemm_zero_offset_and_unsorted_table(any4, oracle):
         run_gemm_case(any4, oracle, M, 192, 1024, 4, seed=77, mutate=mutate)
 
 
+@pytest.mark.parametrize("M", (1, 16, 64))
+def test_gemm_other_4bit_formats_through_the_table(any4, oracle, M):
+    """The paper's other 4-bit formats are tables too (section 4.2, last paragraph): one table shared
+    by all rows (nf4-style) and the uniform integer grid -8 .. 7 (int4) run through the same path."""
+    def shared_table(cs):
+        cs.lut[:] = cs.lut[0]
+    def int4_grid(cs):
+        cs.lut[:] = inputs.f32_to_bf16_bits(np.arange(-8, 8, dtype=np.float32))
+    for mutate in (shared_table, int4_grid):
+        run_gemm_case(any4, oracle, M, 200, 2048, 4, seed=31, mutate=mutate)
+
+
 def test_gemm_is_reproducible(any4, oracle):
     cs = inputs.make_case(4, 64, 16384, 4, seed=12)
     codes = any4.any4_pack(torch.from_numpy(cs.codes_u8).cuda(), 4)
