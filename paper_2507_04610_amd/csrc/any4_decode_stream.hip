@@ -609,13 +609,14 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
             if (gi + 1 < GW) lookups(gi + 1, bq[(gi + 1) & 1]);
             __builtin_amdgcn_sched_barrier(0);
             const uint4 (&b)[4] = bq[gi & 1];
+            // one accumulation chain per group: the scale multiply then needs no extra adds
             f32x4 P0 = mfma(xa[gi][0], b[0], zero);
-            f32x4 P1 = mfma(xa[gi][1], b[1], zero);
+            P0 = mfma(xa[gi][1], b[1], P0);
             P0 = mfma(xa[gi][2], b[2], P0);
-            P1 = mfma(xa[gi][3], b[3], P1);
+            P0 = mfma(xa[gi][3], b[3], P0);
             const float sf = scale_f(sp, gi);
 #pragma unroll
-            for (int v = 0; v < 4; ++v) acc[v] = __builtin_fmaf(P0[v] + P1[v], sf, acc[v]);
+            for (int v = 0; v < 4; ++v) acc[v] = __builtin_fmaf(P0[v], sf, acc[v]);
             __builtin_amdgcn_sched_barrier(0);
         }
         if constexpr (!AUX && REFILL) load_so(sraw[B], oraw[B], tn);
