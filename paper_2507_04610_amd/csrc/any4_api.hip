@@ -2,8 +2,6 @@
 #include "any4.h"
 #include "any4_internal.h"
 #include "any4_splitk.h"
-#include <atomic>
-#include <chrono>
 #include <stdlib.h>
 
 namespace any4 {
@@ -29,15 +27,6 @@ int device_compute_units() {
         return n;
     }();
     return cus;
-}
-
-// Per-call tag for the split-K arrival counters (see any4_splitk.h): 56 bits, never zero, distinct
-// from call to call and, through the clock-derived start value, from earlier processes' left-overs.
-static unsigned long long next_epoch() {
-    static std::atomic<unsigned long long> counter{
-        (unsigned long long)std::chrono::steady_clock::now().time_since_epoch().count() * 0x9E3779B97F4A7C15ull};
-    unsigned long long e = counter.fetch_add(1, std::memory_order_relaxed) & 0x00FFFFFFFFFFFFFFull;
-    return e ? e : 1;
 }
 
 GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int bits) {
@@ -136,7 +125,7 @@ int any4_gemm(const uint16_t* x, const uint32_t* codes, const uint16_t* lut, con
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t e;
     if (plan.stream) {
-        e = launch_decode_stream(x, codes, lut, scale, offset, M, N, K, bits, plan.sp, y, workspace, next_epoch(), s);
+        e = launch_decode_stream(x, codes, lut, scale, offset, M, N, K, bits, plan.sp, y, workspace, s);
     } else if (plan.decode) {
         e = launch_decode(x, codes, lut, scale, offset, M, N, K, bits, plan, y, static_cast<float*>(workspace), s);
     } else {

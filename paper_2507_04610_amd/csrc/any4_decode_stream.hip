@@ -110,7 +110,6 @@ struct Params {
     uint16_t* y;
     float* partial;                  // [slabs][M][N] fp32, slabs > 1 only
     unsigned long long* counters;    // [tiles], slabs > 1 only
-    unsigned long long epoch;
     int64_t N, K;
     int M, G;                        // G = K / 128
     int slabs, slab_groups;          // groups per slab (the last slab may have fewer)
@@ -137,18 +136,29 @@ __device__ __forceinline__ float sum8(const uint4& v) {
 
 // One arrival at a tile's counter by a single thread; true if this was the last of `ksplit`.
 // The caller has made its partial sums visible (stores issued and waited for) beforehand.
-__device__ __forceinline__ bool arrive_one(unsigned long long* c, int ksplit, unsigned long long epoch) {
-    unsigned long long old = __hip_atomic_load(c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+// A counter word is (tag << 8 | arrivals).  The last arrival of a tile puts its counter back to
+// "tag, 0", so a workspace that has served a call is clean for the next one and an arrival is ONE
+// atomic add; a word without the tag (a workspace used for the first time, or memory that held
+// something else) is claimed with a compare-and-swap instead.
+constexpr unsigned long long kArriveTag = 0x00A4C0DE5EED17ull;          // 56 bits
+__device__ __forceinline__ bool arrive_one(unsigned long long* c, int ksplit) {
+    unsigned long long old = __hip_atomic_fetch_add(c, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     unsigned long long cnt;
-    for (;;) {
-        cnt = ((old >> 8) == epoch) ? (old & 0xFFull) + 1ull : 1ull;
-        const unsigned long long nv = (epoch << 8) | cnt;
-        if (__hip_atomic_compare_exchange_strong(c, &old, nv, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
-                                                 __HIP_MEMORY_SCOPE_AGENT))
-            break;
+    if ((old >> 8) == kArriveTag) {
+        cnt = (old & 0xFFull) + 1ull;
+    } else {
+        // the add above went into a foreign word and is dropped with it
+        old += 1ull;
+        for (;;) {
+            cnt = ((old >> 8) == kArriveTag) ? (old & 0xFFull) + 1ull : 1ull;
+            const unsigned long long nv = (kArriveTag << 8) | cnt;
+            if (__hip_atomic_compare_exchange_strong(c, &old, nv, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                                                     __HIP_MEMORY_SCOPE_AGENT))
+                break;
+        }
     }
     const bool last = cnt == (unsigned long long)ksplit;
-    if (last) __hip_atomic_store(c, epoch << 8, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (last) __hip_atomic_store(c, kArriveTag << 8, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     return last;
 }
 
@@ -672,15 +682,17 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
     if (p.slabs > 1) {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's partial sums have been written
         lds_barrier();                                     // ... and so have the whole block's
+        ANY4_STOP(11);
         for (int tb0 = t0; tb0 < t1; tb0 += kListTiles) {      // in rounds of what the list holds
             const int tb1 = min(t1, tb0 + kListTiles);
             for (int i = tb0 + tid; i < tb1; i += kThreads) {
-                if (arrive_one(p.counters + i, p.slabs, p.epoch)) {
+                if (arrive_one(p.counters + i, p.slabs)) {
                     const int slot = atomicAdd(lastlist, 1);
                     lastlist[1 + slot] = i;
                 }
             }
             lds_barrier();
+            ANY4_STOP(12);
             // all outputs of all listed tiles at once, so that the loads of the partial sums overlap
             const int nlast = lastlist[0];
             for (int idx = tid; idx < nlast * M * kTile; idx += kThreads) {
@@ -791,13 +803,12 @@ static hipError_t launch_stream_b(const Params& p, const StreamPlan& sp, int gri
 hipError_t launch_decode_stream(const uint16_t* x, const uint32_t* codes, const uint16_t* lut,
                                 const uint16_t* scale, const uint16_t* offset, int64_t M, int64_t N,
                                 int64_t K, int bits, const StreamPlan& sp, uint16_t* y, void* workspace,
-                                unsigned long long epoch, hipStream_t stream) {
+                                hipStream_t stream) {
     Params p{};
     p.x = x; p.codes = codes; p.lut = lut; p.scale = scale; p.offset = offset; p.y = y;
     p.counters = static_cast<unsigned long long*>(workspace);
     p.partial = sp.slabs > 1
         ? reinterpret_cast<float*>(static_cast<char*>(workspace) + splitk_counter_bytes(sp.tiles)) : nullptr;
-    p.epoch = epoch;
     p.N = N; p.K = K; p.M = (int)M; p.G = (int)(K / kGroup);
     p.slabs = sp.slabs; p.slab_groups = sp.slab_groups; p.blocks_per_slab = sp.blocks_per_slab;
     p.tiles = (int)sp.tiles;

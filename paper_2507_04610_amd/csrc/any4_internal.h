@@ -42,7 +42,7 @@ hipError_t launch_decode(const uint16_t* x, const uint32_t* codes, const uint16_
 hipError_t launch_decode_stream(const uint16_t* x, const uint32_t* codes, const uint16_t* lut,
                                 const uint16_t* scale, const uint16_t* offset, int64_t M, int64_t N,
                                 int64_t K, int bits, const StreamPlan& sp, uint16_t* y, void* workspace,
-                                unsigned long long epoch, hipStream_t stream);
+                                hipStream_t stream);
 hipError_t launch_reduce_slices(const float* partial, int ksplit, int64_t MN, uint16_t* y, hipStream_t stream);
 hipError_t launch_prefill(const uint16_t* x, const uint32_t* codes, const uint16_t* lut,
                           const uint16_t* scale, const uint16_t* offset,

@@ -4,11 +4,12 @@
 // has finished all its tiles, bumps each tile's arrival counter.  The block that arrives last at a
 // tile adds the partials of ALL slabs in slab order - so the result does not depend on which
 // block happened to be last - rounds to bf16 and stores y.  Counters live at the start of the
-// workspace as 64-bit words (epoch << 8 | arrivals).  The epoch is a per-call number chosen on
-// the host: a counter whose epoch differs from the current call's is stale (left-over or
-// never-initialised memory) and counts as zero, so the workspace needs no initialisation.  The
-// last block puts the counter back to (epoch, 0), which keeps a captured launch valid for any
-// number of graph replays.  The arrival itself is in any4_decode_stream.hip.
+// workspace as 64-bit words (tag << 8 | arrivals) with a fixed 56-bit tag.  A word that does not
+// carry the tag (never-initialised memory, or memory an earlier call used for something else)
+// counts as zero arrivals, so the workspace needs no initialisation; the last block puts the
+// counter back to (tag, 0), so every completed call leaves its counters clean - for the next call
+// and for any number of replays of a captured launch.  The arrival itself is in
+// any4_decode_stream.hip.
 #pragma once
 #include "any4_device.h"
 
