@@ -82,13 +82,6 @@ __global__ __launch_bounds__(PTHREADS, 1) void prefill_kernel(
     const int64_t m0 = (int64_t)blockIdx.x * PBM, n0 = (int64_t)blockIdx.y * PBN;
     const int64_t G = K / kGroup, RW = row_words(K, BITS);
 
-    // per-row tables of this block's weight rows (rows past N are clamped: they are never stored)
-    for (int i = tid; i < PBN * L * 4; i += PTHREADS) {
-        const int cp = i & 3, r = (i >> 2) & 7, c = (i >> 5) & (L - 1), blk = i >> (5 + BITS);
-        table[i] = lut[min(n0 + blk * 8 + r, N - 1) * L + c];
-        (void)cp;
-    }
-
     // weight slab: thread -> (row, 16-code quarter of the K step)
     const int wrow = tid >> 2, wq = tid & 3;
     const int64_t wn_glob = min(n0 + wrow, N - 1);
@@ -196,7 +189,23 @@ __global__ __launch_bounds__(PTHREADS, 1) void prefill_kernel(
 
     // ---- main loop over groups of 128 (two K steps each).  While the matrix cores work on one buffer,
     //      the next K step (fetched before the MFMAs were issued) is looked up and written to the other.
-    fetch_main(0);
+    fetch_main(0);                                             // in flight while the tables are filled
+    // per-row tables of this block's weight rows (rows past N are clamped: they are never stored):
+    // one thread fetches 8 bytes (4 entries) of a row and writes each entry's 4 adjacent copies at once
+    {
+        constexpr int PIECES = L / 4;                            // 8-byte pieces per row
+        for (int i = tid; i < PBN * PIECES; i += PTHREADS) {
+            const int row = i / PIECES, pc = i % PIECES;
+            const uint2 v = *reinterpret_cast<const uint2*>(lut + min(n0 + row, N - 1) * L + pc * 4);
+            uint32_t* dst = table + (row >> 3) * (32 << BITS) + (pc * 4) * 32 + (row & 7) * 4;
+            const uint32_t e0 = v.x & 0xFFFFu, e1 = v.x >> 16, e2 = v.y & 0xFFFFu, e3 = v.y >> 16;
+            *reinterpret_cast<uint4*>(dst) = make_uint4(e0, e0, e0, e0);
+            *reinterpret_cast<uint4*>(dst + 32) = make_uint4(e1, e1, e1, e1);
+            *reinterpret_cast<uint4*>(dst + 64) = make_uint4(e2, e2, e2, e2);
+            *reinterpret_cast<uint4*>(dst + 96) = make_uint4(e3, e3, e3, e3);
+        }
+    }
+
     __syncthreads();                                           // tables are written
     stage_x(0);
     stage_w_main(0);
