@@ -354,6 +354,24 @@ def main():
             del rot, wb
             torch.cuda.empty_cache()
         extras["square_1xK_KxK"] = sq
+        # the paper's format comparison (section 5, "Speed Comparisons"): the same Llama-3-8B linears at
+        # M = 1 as any4 (a table per row), with one table shared by all rows (nf4-style: the same
+        # kernel, the table rows simply repeat) and as int4 (lut = NULL: no table at all)
+        fm = {}
+        for gi, g in enumerate(layers_keep):
+            copies = max(2, min(16, int(1.2e9 // (g["N"] * g["K"] // 2)) + 1))
+            rot = [make_layer({g["name"]: (g["N"], g["K"])}, 1, seed=950 + c)[0] for c in range(copies)]
+
+            def call(p_, lut_):
+                return lambda: any4.any4_gemm(p_["x"], p_["codes"], lut_, p_["scale"], p_["offset"], bits,
+                                              out=p_["y"], workspace=p_["ws"])
+            shared = [p_["lut"][:1].expand(p_["N"], -1).contiguous() for p_ in rot]
+            fm[g["name"]] = {"any4_us": graph_us([call(p_, p_["lut"]) for p_ in rot]),
+                             "shared_table_us": graph_us([call(p_, sh) for p_, sh in zip(rot, shared)]),
+                             "int4_no_table_us": graph_us([call(p_, None) for p_ in rot])}
+            del rot, shared
+            torch.cuda.empty_cache()
+        extras["formats_llama3_8b_M1"] = fm
         layers = [layers_keep]
 
     # ------------------------------------------------------------------ CPU oracle beside it

@@ -65,7 +65,10 @@ int any4_pack(const uint8_t* codes_u8, int64_t N, int64_t K, int bits,
  *     w[n][k] = fma(LUT[n][code], scale[n][k/128], offset[n][k/128])
  * evaluated in fp32 with a single rounding; the result is defined bit for bit.
  *   codes   in   uint32 [N][K*bits/32]
- *   lut     in   bf16   [N][2^bits]   the row's table; entry order carries no meaning
+ *   lut     in   bf16   [N][2^bits]   the row's table; entry order carries no meaning.
+ *                With bits = 4, lut may be NULL: the table of every row is then the integer
+ *                grid -8 .. 7 (value = code - 8), the uniform int4 format the paper compares
+ *                with (section 4.2, last paragraph); any4_gemm runs it without any table.
  *   scale   in   bf16   [N][K/128]
  *   offset  in   bf16   [N][K/128]
  *   w       out  fp32   [N][K], fully overwritten
@@ -82,6 +85,7 @@ int any4_dequant(const uint32_t* codes, const uint16_t* lut, const uint16_t* sca
  * Small M (<= 16, token generation) takes a memory-bound kernel, larger M a
  * matrix-core kernel; the choice depends only on (M, N, K, bits).
  *   x          in   bf16 [M][K]
+ *   lut        as for any4_dequant, including NULL = int4 grid for bits = 4
  *   y          out  bf16 [M][N], fully overwritten
  *   workspace  scratch of at least any4_gemm_workspace_bytes(M, N, K, bits) bytes,
  *              16-byte aligned; may be NULL when that size is 0.  Contents on entry

@@ -107,13 +107,13 @@ def any4_pack(codes_u8: torch.Tensor, bits: int = 4, out: torch.Tensor | None = 
     return out
 
 
-def any4_dequant(codes: torch.Tensor, lut: torch.Tensor, scale: torch.Tensor, offset: torch.Tensor,
+def any4_dequant(codes: torch.Tensor, lut: torch.Tensor | None, scale: torch.Tensor, offset: torch.Tensor,
                  K: int, bits: int = 4, out: torch.Tensor | None = None) -> torch.Tensor:
-    """fp32 [N,K] dequantised weights."""
+    """fp32 [N,K] dequantised weights (lut None with bits 4: the int4 grid, value = code - 8)."""
     lib = load_library()
     N = codes.shape[0]
     pc = _dev(codes, torch.int32, "codes")
-    pl = _dev(lut, torch.bfloat16, "lut")
+    pl = _dev(lut, torch.bfloat16, "lut") if lut is not None else None
     ps = _dev(scale, torch.bfloat16, "scale")
     po = _dev(offset, torch.bfloat16, "offset")
     if out is None:
@@ -123,16 +123,17 @@ def any4_dequant(codes: torch.Tensor, lut: torch.Tensor, scale: torch.Tensor, of
     return out
 
 
-def any4_gemm(x: torch.Tensor, codes: torch.Tensor, lut: torch.Tensor, scale: torch.Tensor,
+def any4_gemm(x: torch.Tensor, codes: torch.Tensor, lut: torch.Tensor | None, scale: torch.Tensor,
               offset: torch.Tensor, bits: int = 4, out: torch.Tensor | None = None,
               workspace: torch.Tensor | None = None) -> torch.Tensor:
-    """bf16 [M,N] = x[M,K] . dequant(codes, lut, scale, offset)[N,K]^T."""
+    """bf16 [M,N] = x[M,K] . dequant(codes, lut, scale, offset)[N,K]^T
+    (lut None with bits 4: the int4 grid, value = code - 8, run without a table)."""
     lib = load_library()
     M, K = x.shape
     N = codes.shape[0]
     px = _dev(x, torch.bfloat16, "x")
     pc = _dev(codes, torch.int32, "codes")
-    pl = _dev(lut, torch.bfloat16, "lut")
+    pl = _dev(lut, torch.bfloat16, "lut") if lut is not None else None
     ps = _dev(scale, torch.bfloat16, "scale")
     po = _dev(offset, torch.bfloat16, "offset")
     if out is None:

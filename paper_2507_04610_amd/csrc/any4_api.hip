@@ -74,7 +74,8 @@ int any4_pack(const uint8_t* codes_u8, int64_t N, int64_t K, int bits, uint32_t*
 
 int any4_dequant(const uint32_t* codes, const uint16_t* lut, const uint16_t* scale,
                  const uint16_t* offset, int64_t N, int64_t K, int bits, float* w, void* stream) {
-    if (!codes || !lut || !scale || !offset || !w) return ANY4_ERR_NULL;
+    if (!codes || !scale || !offset || !w) return ANY4_ERR_NULL;
+    if (!lut && bits != 4) return ANY4_ERR_NULL;           // no table = the 4-bit integer grid only
     if (int rc = shape_check(N, K, bits)) return rc;
     if (!aligned16(codes) || !aligned16(lut) || !aligned16(scale) || !aligned16(offset) || !aligned16(w))
         return ANY4_ERR_ALIGN;
@@ -114,7 +115,8 @@ size_t any4_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int bits) {
 int any4_gemm(const uint16_t* x, const uint32_t* codes, const uint16_t* lut, const uint16_t* scale,
               const uint16_t* offset, int64_t M, int64_t N, int64_t K, int bits, uint16_t* y,
               void* workspace, size_t workspace_bytes, void* stream) {
-    if (!x || !codes || !lut || !scale || !offset || !y) return ANY4_ERR_NULL;
+    if (!x || !codes || !scale || !offset || !y) return ANY4_ERR_NULL;
+    if (!lut && bits != 4) return ANY4_ERR_NULL;           // no table = the 4-bit integer grid only
     if (int rc = shape_check(N, K, bits)) return rc;
     if (M < 1) return ANY4_ERR_SHAPE;
     if (!aligned16(x) || !aligned16(codes) || !aligned16(lut) || !aligned16(scale) ||

@@ -43,7 +43,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64) void decode_rows_kernel(
     const bool active = n < N;                      // whole wave takes the same branch
     const int64_t nn = active ? n : 0;
 
-    if (lane < L) table[wave][lane] = bf16_to_f32(lut[nn * L + lane]);
+    if (lane < L) table[wave][lane] = lut ? bf16_to_f32(lut[nn * L + lane]) : (float)(lane - L / 2);   // no table: the integer grid
     __syncthreads();                                // one barrier, reached by every wave
     if (!active) return;
 

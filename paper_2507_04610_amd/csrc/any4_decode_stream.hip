@@ -166,8 +166,13 @@ __device__ __forceinline__ bool arrive_one(unsigned long long* c, int ksplit) {
 // GW      groups (of 128 weights) a wavefront owns: 1, 2 or 4
 // AUX     tables, scales and offsets of a tile are loaded by one wavefront and shared through LDS;
 //         requires K/128 and the slab size to be multiples of 4 (8-byte aligned loads)
-template <int BITS, int GW, bool AUX>
+// NOLUT   4-bit codes on the uniform grid (value = code - 8, the int4 format): no table at all.
+//         A code c becomes the bf16 number 128 + c by OR-ing it into the mantissa of 128.0
+//         (0x4300 | c), and the surplus 136 * scale * (group sum of x) is taken off again by two more
+//         exact bf16 terms (-128 * scale and -8 * scale) that ride in the offset MFMA.
+template <int BITS, int GW, bool AUX, bool NOLUT>
 __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Params p) {
+    static_assert(!NOLUT || BITS == 4, "the table-free path is the 4-bit integer grid");
     static_assert(BITS == 4 || BITS == 3 || BITS == 2, "code width");
     static_assert(kDepth == 4 || kDepth == 2, "the tile loop is unrolled by kDepth");
     constexpr int WAVES = kWaves, kThreads = WAVES * 64;
@@ -256,7 +261,9 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
     const uint32_t lut_hi_off = BITS == 4 ? (uint32_t)w * 4u : (uint32_t)(w >> 1) * 4u;
     // reads a LutSrc from a row of the table, in memory or in an LDS slot (same code, any pointer)
     auto read_lut_row = [&](LutSrc& l, const char* row) {
-        if constexpr (BITS == 4) {
+        if constexpr (NOLUT) {
+            (void)l; (void)row;
+        } else if constexpr (BITS == 4) {
             const uint4 v = *reinterpret_cast<const uint4*>(row + lut_lo_off);
             l.a[0] = v.x; l.a[1] = v.y; l.a[2] = v.z; l.a[3] = v.w;
             l.h = *reinterpret_cast<const uint32_t*>(row + lut_hi_off);
@@ -274,7 +281,9 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
     // table of a tile into buffer `par`
     auto build_table = [&](const LutSrc& l, int par) {
         uint32_t* const tab = reinterpret_cast<uint32_t*>(smem);
-        if constexpr (BITS == 4) {
+        if constexpr (NOLUT) {
+            (void)l; (void)par; (void)tab;
+        } else if constexpr (BITS == 4) {
             // entry e of row n at dword e * 64 + par * 32 + n * 2, both copies
             const uint32_t hv = (q & 2) ? (l.h & 0xFFFF0000u) : (l.h << 16);
             uint32_t* dst = tab + ((2 * w + (q >> 1)) * 16 + 8 * (q & 1)) * 64 + par * 32 + n * 2;
@@ -322,7 +331,8 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
                 axo[c] = *reinterpret_cast<const uint2*>(offset_b + tile_off + c * 32 + vs);
             }
         const char* lrow = lut_b + (int64_t)t * (kTile * LUTB) + (t == last_tile ? vl_last : vl_norm);
-        if constexpr (BITS == 4) { if (q < 2) axl = *reinterpret_cast<const uint4*>(lrow + q * 16); }
+        if constexpr (NOLUT) { (void)lrow; }
+        else if constexpr (BITS == 4) { if (q < 2) axl = *reinterpret_cast<const uint4*>(lrow + q * 16); }
         else if constexpr (BITS == 3) { if (q < 1) axl = *reinterpret_cast<const uint4*>(lrow); }
         else { if (q < 1) { const uint2 v = *reinterpret_cast<const uint2*>(lrow); axl.x = v.x; axl.y = v.y; } }
     };
@@ -334,7 +344,8 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
                 *reinterpret_cast<uint2*>(s + kAuxScale + n * kAuxRow + (c * 4 + q) * 8) = axs[c];
                 *reinterpret_cast<uint2*>(s + kAuxOffset + n * kAuxRow + (c * 4 + q) * 8) = axo[c];
             }
-        if constexpr (BITS == 4) { if (q < 2) *reinterpret_cast<uint4*>(s + kAuxLut + n * 32 + q * 16) = axl; }
+        if constexpr (NOLUT) { }
+        else if constexpr (BITS == 4) { if (q < 2) *reinterpret_cast<uint4*>(s + kAuxLut + n * 32 + q * 16) = axl; }
         else if constexpr (BITS == 3) { if (q < 1) *reinterpret_cast<uint4*>(s + kAuxLut + n * 32) = axl; }
         else { if (q < 1) *reinterpret_cast<uint2*>(s + kAuxLut + n * 32) = make_uint2(axl.x, axl.y); }
     };
@@ -388,6 +399,16 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
     // (slots of groups the wavefront does not have are zero and meet zero activation sums)
     auto offset_operand = [&](const uint32_t (&op)[NP]) -> uint4 {
         const uint32_t a = op[0], b = NP > 1 ? op[NP - 1] : 0u;
+        return make_uint4(a, b, a, b);
+    };
+    // NOLUT: lanes of quarter 0 carry the offsets, quarter 1 carries -128 * scale and quarter 2
+    // -8 * scale (exponent + 7 / + 3 and the sign flipped, on both bf16 halves of a word: exact);
+    // all three meet the same group sums of x
+    auto offset_operand_nolut = [&](const uint32_t (&sp)[NP], const uint32_t (&op)[NP]) -> uint4 {
+        uint32_t a = op[0], b = NP > 1 ? op[NP - 1] : 0u;
+        const uint32_t sa = sp[0], sb = NP > 1 ? sp[NP - 1] : 0u;
+        if (q == 1) { a = (sa + 0x03800380u) ^ 0x80008000u; b = (sb + 0x03800380u) ^ 0x80008000u; }
+        if (q == 2) { a = (sa + 0x01800180u) ^ 0x80008000u; b = (sb + 0x01800180u) ^ 0x80008000u; }
         return make_uint4(a, b, a, b);
     };
 
@@ -493,7 +514,18 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
             lo[gi] = f32_to_bf16(sgi - bf16_to_f32(hi[gi]));
         }
         xo = make_uint4(hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16), lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16));
-        if (q) xo = make_uint4(0, 0, 0, 0);
+        if (NOLUT ? q > 2 : q > 0) xo = make_uint4(0, 0, 0, 0);
+    }
+    if constexpr (NOLUT) {
+        // operand order of the table-free path: elements (0, 4), (1, 5), (2, 6), (3, 7) of every 8
+#pragma unroll
+        for (int gi = 0; gi < GW; ++gi)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint4 v = xa[gi][j];
+                xa[gi][j] = make_uint4(__builtin_amdgcn_perm(v.z, v.x, 0x05040100u), __builtin_amdgcn_perm(v.z, v.x, 0x07060302u),
+                                       __builtin_amdgcn_perm(v.w, v.y, 0x05040100u), __builtin_amdgcn_perm(v.w, v.y, 0x07060302u));
+            }
     }
     ANY4_STOP(5);
     if constexpr (AUX) {
@@ -521,7 +553,16 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
     // `low` = the lane's fixed part of a table address (row, copy and table buffer).
     auto lookup = [&](const Quarter& c, int j, uint32_t low) -> uint4 {
         uint4 b;
-        if constexpr (BITS == 4) {
+        if constexpr (NOLUT) {
+            // nibbles n0..n7 of the word -> bf16 pairs (128 + n0, 128 + n4), (n1, n5), (n2, n6), (n3, n7);
+            // the activations were put into the same order before the loop
+            const uint32_t wd = c.w[j];
+            b.x = (wd & 0x000F000Fu) | 0x43004300u;
+            b.y = ((wd >> 4) & 0x000F000Fu) | 0x43004300u;
+            b.z = ((wd >> 8) & 0x000F000Fu) | 0x43004300u;
+            b.w = ((wd >> 12) & 0x000F000Fu) | 0x43004300u;
+            (void)low;
+        } else if constexpr (BITS == 4) {
             const uint32_t wd = c.w[j];
             b.x = *reinterpret_cast<lds_u32>(__builtin_amdgcn_perm(wd, low, 0x0c0c0400u));
             b.y = *reinterpret_cast<lds_u32>(__builtin_amdgcn_perm(wd, low, 0x0c0c0500u));
@@ -613,7 +654,7 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
             if (i + 1 < ntiles) build_table(lut_ring[B1], par ^ 1);
             if constexpr (REFILL) load_lut(lut_ring[B1], min(t + 1 + kDepth, t1 - 1));
         }
-        f32x4 acc = mfma(xo, offset_operand(op), zero);
+        f32x4 acc = mfma(xo, NOLUT ? offset_operand_nolut(sp, op) : offset_operand(op), zero);
 #pragma unroll
         for (int gi = 0; gi < GW; ++gi) {
             if (gi + 1 < GW) lookups(gi + 1, bq[(gi + 1) & 1]);
@@ -773,9 +814,9 @@ StreamPlan plan_stream(int64_t M, int64_t N, int64_t K, int cus) {
     return best;
 }
 
-template <int BITS, int GW, bool AUX>
+template <int BITS, int GW, bool AUX, bool NOLUT = false>
 static hipError_t launch_stream_t(const Params& p, int grid, hipStream_t stream) {
-    auto kern = stream::decode_stream_kernel<BITS, GW, AUX>;
+    auto kern = stream::decode_stream_kernel<BITS, GW, AUX, NOLUT>;
 #ifdef ANY4_STAMPS
     constexpr int lds = stream::lds_bytes(BITS) + stream::kWaves * stream::kStampSteps * 4 * 8;
 #else
@@ -816,6 +857,16 @@ hipError_t launch_decode_stream(const uint16_t* x, const uint32_t* codes, const 
     if (const char* e = getenv("ANY4_TUNE_STOP")) p.stop = atoi(e);
 #endif
     const int grid = sp.slabs * sp.blocks_per_slab;
+    if (bits == 4 && lut == nullptr) {                     // the integer grid: no table
+#define ANY4_STREAM_NL(GW)                                                                 \
+    (sp.aux ? launch_stream_t<4, GW, true, true>(p, grid, stream) : launch_stream_t<4, GW, false, true>(p, grid, stream))
+        switch (sp.gw) {
+            case 4: return ANY4_STREAM_NL(4);
+            case 2: return ANY4_STREAM_NL(2);
+            default: return ANY4_STREAM_NL(1);
+        }
+#undef ANY4_STREAM_NL
+    }
     if (bits == 4) return launch_stream_b<4>(p, sp, grid, stream);
     if (bits == 3) return launch_stream_b<3>(p, sp, grid, stream);
     return launch_stream_b<2>(p, sp, grid, stream);

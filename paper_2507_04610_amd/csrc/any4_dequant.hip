@@ -20,7 +20,7 @@ __global__ __launch_bounds__(256) void dequant_kernel(const uint32_t* __restrict
     constexpr uint32_t mask = L - 1;
     __shared__ float table[L];
     const int64_t n = blockIdx.x;
-    if (threadIdx.x < L) table[threadIdx.x] = bf16_to_f32(lut[n * L + threadIdx.x]);
+    if (threadIdx.x < L) table[threadIdx.x] = lut ? bf16_to_f32(lut[n * L + threadIdx.x]) : (float)((int)threadIdx.x - L / 2);   // no table: the integer grid
     __syncthreads();
 
     const uint32_t* row = codes + n * row_words(K, BITS);

@@ -196,7 +196,13 @@ __global__ __launch_bounds__(PTHREADS, 1) void prefill_kernel(
         constexpr int PIECES = L / 4;                            // 8-byte pieces per row
         for (int i = tid; i < PBN * PIECES; i += PTHREADS) {
             const int row = i / PIECES, pc = i % PIECES;
-            const uint2 v = *reinterpret_cast<const uint2*>(lut + min(n0 + row, N - 1) * L + pc * 4);
+            uint2 v;
+            if (lut) v = *reinterpret_cast<const uint2*>(lut + min(n0 + row, N - 1) * L + pc * 4);
+            else {                                             // no table: the integer grid, entries pc * 4 .. + 3
+                const int c0 = pc * 4 - L / 2;
+                v.x = f32_to_bf16((float)c0) | (f32_to_bf16((float)(c0 + 1)) << 16);
+                v.y = f32_to_bf16((float)(c0 + 2)) | (f32_to_bf16((float)(c0 + 3)) << 16);
+            }
             uint32_t* dst = table + (row >> 3) * (32 << BITS) + (pc * 4) * 32 + (row & 7) * 4;
             const uint32_t e0 = v.x & 0xFFFFu, e1 = v.x >> 16, e2 = v.y & 0xFFFFu, e3 = v.y >> 16;
             *reinterpret_cast<uint4*>(dst) = make_uint4(e0, e0, e0, e0);

@@ -180,6 +180,33 @@ def test_gemm_other_4bit_formats_through_the_table(any4, oracle, M):
         run_gemm_case(any4, oracle, M, 200, 2048, 4, seed=31, mutate=mutate)
 
 
+@pytest.mark.parametrize("M,N,K", [(1, 333, 4224), (1, 64, 128), (3, 17, 384), (8, 700, 640), (16, 100, 4480),
+                                   (2, 48, 14336), (16, 33, 8192), (40, 200, 1024), (300, 130, 640)])
+def test_gemm_int4_grid_without_table(any4, oracle, M, N, K):
+    """lut = NULL with 4-bit codes: the uniform integer grid (value = code - 8).  The oracle runs the
+    same problem with that grid written out as every row's table; the device runs it table-free
+    (M <= 16) or with the grid synthesised inside the kernel (larger M), and the dequantised weights
+    agree bit for bit."""
+    cs = inputs.make_case(M, N, K, 4, seed=inputs.case_seed(11, 4, M % 10))
+    cs.lut[:] = inputs.f32_to_bf16_bits(np.arange(-8, 8, dtype=np.float32))
+    packed = oracle.pack(cs.codes_u8, 4)
+    y64 = oracle.gemm(cs.x, packed, cs.lut, cs.scale, cs.offset, K, 4, threads=8)
+    codes_dev = any4.any4_pack(torch.from_numpy(cs.codes_u8).cuda(), 4)
+    y = any4.any4_gemm(dev_bf16(cs.x), codes_dev, None, dev_bf16(cs.scale), dev_bf16(cs.offset), 4)
+    torch.cuda.synchronize()
+    check_gemm(y, y64, oracle.rms(y64), ("int4", M, N, K))
+    w = any4.any4_dequant(codes_dev, None, dev_bf16(cs.scale), dev_bf16(cs.offset), K, 4)
+    assert np.array_equal(host_u32(w), oracle.dequant(packed, cs.lut, cs.scale, cs.offset, K, 4).view(np.uint32))
+
+
+def test_no_table_needs_four_bits(any4):
+    from paper_2507_04610_amd import binding
+    cs = inputs.make_case(1, 16, 128, 3, seed=1)
+    codes_dev = any4.any4_pack(torch.from_numpy(cs.codes_u8).cuda(), 3)
+    with pytest.raises(binding.Any4Error):
+        any4.any4_gemm(dev_bf16(cs.x), codes_dev, None, dev_bf16(cs.scale), dev_bf16(cs.offset), 3)
+
+
 def test_gemm_is_reproducible(any4, oracle):
     cs = inputs.make_case(4, 64, 16384, 4, seed=12)
     codes = any4.any4_pack(torch.from_numpy(cs.codes_u8).cuda(), 4)
