@@ -52,7 +52,10 @@ def test_bad_arguments_are_rejected_before_any_launch(lib):
     A = 0x1000          # fake, 16-byte aligned, never dereferenced: validation fails first
     # NULL pointers
     assert lib.any4_pack(None, 4, 128, 4, A, None) == -1
-    assert lib.any4_dequant(A, None, A, A, 4, 128, 4, A, None) == -1
+    assert lib.any4_dequant(A, A, None, A, 4, 128, 4, A, None) == -1
+    # a NULL table selects the 4-bit integer grid and is an error for any other width
+    assert lib.any4_dequant(A, None, A, A, 4, 128, 3, A, None) == -1
+    assert lib.any4_gemm(A, A, None, A, A, 1, 4, 128, 2, A, None, 0, None) == -1
     assert lib.any4_gemm(A, A, A, A, A, 1, 4, 128, 4, None, None, 0, None) == -1
     # shapes
     assert lib.any4_pack(A, 0, 128, 4, A, None) == -2
