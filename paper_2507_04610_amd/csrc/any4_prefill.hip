@@ -6,9 +6,9 @@
 // sections 2.4.1 / 2.5.2 define the table lookup and alpha * w_Q + beta).  The paper's own
 // kernels stop at M = 16; this path is the large-M counterpart for CDNA4.
 //
-// Rounding a dequantised weight to bf16 would cost up to 2^-8 relative per weight, which is too
-// much for the 1e-2 * rms output bound.  The kernel therefore never forms w.  Per group g of
-// 128 weights it uses
+// Rounding a dequantised weight to bf16 costs up to 2^-8 relative per weight (1.7e-3 rms of the
+// output, ~1e-2 * rms at the worst of a few million outputs), which is too much for the
+// 1e-2 * rms output bound.  The kernel therefore never forms w.  Per group g of 128 weights it uses
 //     sum_{k in g} x[m][k] w[n][k] = scale[n][g] * sum_{k in g} x[m][k] LUT[n][code[n][k]]
 //                                  + offset[n][g] * X[m][g],      X[m][g] = sum_{k in g} x[m][k]
 // The first sum multiplies two exact bf16 operands on the matrix cores (fp32 accumulate) and is
@@ -17,10 +17,14 @@
 // (relative error 2^-16), and whose right operand is the bf16 offset itself.
 //
 // Block tile 256 (m) x 128 (n), K step 64, eight wavefronts in a 4 x 2 arrangement, each owning a
-// 64 x 64 sub-tile as 2 x 2 v_mfma_f32_32x32x16_bf16 accumulators.  Two LDS buffers: while the
-// matrix cores work on K step s, the activations and codes of step s+1 are already in registers
-// (loaded before the MFMAs were issued) and are looked up / written to the other buffer behind
-// them; one barrier per K step.
+// 64 x 64 sub-tile as 2 x 2 v_mfma_f32_32x32x16_bf16 accumulators.  Two LDS buffers and one barrier
+// per K step.  A K step is written as ONE software-pipelined instruction stream whose order is
+// pinned (scheduling barriers): the 16 MFMAs of the step on buffer b are interleaved with
+// everything that prepares the next step in buffer b^1 - operand reads one 16-wide slice ahead,
+// the table lookups, packing and the LDS writes of the activation tile and of the looked-up tile,
+// the per-group scale fold - while the global loads of later steps are in flight.  Left to
+// itself the compiler emits "all MFMAs, then all staging", and the two wavefronts of a SIMD, which
+// the barrier keeps in step, then leave the matrix cores idle while both stage.
 #include "any4_device.h"
 #include "any4_internal.h"
 #include <type_traits>
@@ -29,10 +33,20 @@ namespace any4 {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) u32x4* lds_u4;
+typedef const __attribute__((address_space(3))) uint32_t* lds_u32;
 
 constexpr int PBM = 256, PBN = 128, PBK = 64;
 constexpr int PTHREADS = 512;
 constexpr int PLD = PBK + 8;          // LDS row stride in bf16 elements (144 B: keeps 16-byte reads spread over banks)
+constexpr uint32_t kXBuf = PBM * PLD * 2, kWBuf = PBN * PLD * 2;   // bytes of one activation / weight buffer
+constexpr uint32_t kTableOff = 2 * kXBuf + 2 * kWBuf;              // 110592 = 0x1B000: the low 12 bits are clear
+
+__device__ __forceinline__ void lds_barrier() {                 // outstanding global loads stay in flight
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+#define ANY4_SB() __builtin_amdgcn_sched_barrier(0)
 
 // X[m][g] = sum of the 128 activations of group g, in fp32, stored as two bf16 (high part,
 // remainder) at xs[m][2g], xs[m][2g+1]; columns 2G .. KP-1 are zero.  16 lanes per (m, g).
@@ -64,7 +78,8 @@ __global__ __launch_bounds__(256) void group_sums_kernel(const uint16_t* __restr
 
 // LDS copy of the block's row tables, laid out so that the 32 lanes LDS serves together never share
 // a bank: a half-wavefront holds 8 rows x 4 quarter-threads, and entry c of (row, quarter) lives at
-// dword (row / 8) * (32 << BITS) + c * 32 + (row % 8) * 4 + quarter (every row is stored 4 times).
+// dword (row / 8) * (32 << BITS) + c * 32 + (row % 8) * 4 + quarter (every row is stored 4 times;
+// the bf16 value sits in the low half of the dword).
 template <int BITS>
 __global__ __launch_bounds__(PTHREADS, 1) void prefill_kernel(
     const uint16_t* __restrict__ x, const uint32_t* __restrict__ codes,
@@ -73,34 +88,36 @@ __global__ __launch_bounds__(PTHREADS, 1) void prefill_kernel(
     int64_t M, int64_t N, int64_t K, uint16_t* __restrict__ y) {
     constexpr int L = 1 << BITS;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    uint16_t* xs = reinterpret_cast<uint16_t*>(smem);                              // [2][PBM][PLD]
-    uint16_t* ws = xs + 2 * PBM * PLD;                                             // [2][PBN][PLD]
-    uint32_t* table = reinterpret_cast<uint32_t*>(ws + 2 * PBN * PLD);             // [PBN / 8][L][32], bf16 value in the low half
+    uint32_t* table = reinterpret_cast<uint32_t*>(smem + kTableOff);      // [PBN / 8][L][32]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int64_t m0 = (int64_t)blockIdx.x * PBM, n0 = (int64_t)blockIdx.y * PBN;
     const int64_t G = K / kGroup, RW = row_words(K, BITS);
+    const int T = (int)(2 * G);                                           // K steps
 
-    // weight slab: thread -> (row, 16-code quarter of the K step)
+    // ---- staging roles.  Weights: thread -> (row, 16-code quarter of the K step); rows past N are
+    //      clamped (computed, never stored).  Activations: thread -> 4 rows, one 16-byte piece each.
     const int wrow = tid >> 2, wq = tid & 3;
     const int64_t wn_glob = min(n0 + wrow, N - 1);
     // word offset / bit shift of the thread's 16 codes inside the K step's (2 * BITS)-word chunk
     const int qword = BITS == 4 ? 2 * wq : (BITS == 2 ? wq : (6 * wq) >> 2);
     const int qshift = BITS == 3 ? ((6 * wq) & 3) * 8 : 0;
-    const uint32_t* wsrc = codes + wn_glob * RW + qword;
-    // LDS byte address of this thread's entry 0 (the kernel has no static LDS: dynamic LDS starts at 0)
-    const uint32_t tbase = (uint32_t)((2 * PBM * PLD + 2 * PBN * PLD) * 2 + ((wrow >> 3) * (32 << BITS) + (wrow & 7) * 4 + wq) * 4);
-    typedef const __attribute__((address_space(3))) uint32_t* lds_u32;
-    // activation slab: thread -> 4 rows (256 rows / 64), one 16-byte column piece
+    const uint32_t* const wsrc = codes + wn_glob * RW + qword;
     const int xr_row = tid >> 3, xc8 = tid & 7;
-    int64_t xm[4];                                                          // rows past M are clamped, never stored
+    const uint16_t* xsrc[4];                                              // rows past M are clamped, never stored
 #pragma unroll
-    for (int pi = 0; pi < 4; ++pi) xm[pi] = min(m0 + pi * 64 + xr_row, M - 1);
+    for (int p = 0; p < 4; ++p) xsrc[p] = x + min(m0 + p * 64 + xr_row, M - 1) * K + xc8 * 8;
     // the two output columns this lane owns (one per 32-wide n tile of its wavefront)
     const uint16_t* scol[2];
 #pragma unroll
     for (int j = 0; j < 2; ++j) scol[j] = scale + min(n0 + wn * 64 + j * 32 + (lane & 31), N - 1) * G;
+    // LDS byte addresses (the kernel has no static LDS: dynamic LDS starts at 0)
+    const uint32_t tbase = kTableOff + (uint32_t)((wrow >> 3) * (32 << BITS) + (wrow & 7) * 4 + wq) * 4u;
+    const uint32_t xwr = (uint32_t)(xr_row * PLD + xc8 * 8) * 2u;                         // + buf * kXBuf + p * 64 rows
+    const uint32_t wwr = 2 * kXBuf + (uint32_t)(wrow * PLD + wq * 16) * 2u;               // + buf * kWBuf + chunk * 16
+    const uint32_t ard = (uint32_t)((wm * 64 + (lane & 31)) * PLD + (lane >> 5) * 8) * 2u;
+    const uint32_t brd = 2 * kXBuf + (uint32_t)((wn * 64 + (lane & 31)) * PLD + (lane >> 5) * 8) * 2u;
 
     f32x16 acc[2][2], part[2][2];
     f32x16 zero;
@@ -111,85 +128,134 @@ __global__ __launch_bounds__(PTHREADS, 1) void prefill_kernel(
 #pragma unroll
         for (int j = 0; j < 2; ++j) { acc[i][j] = zero; part[i][j] = zero; }
 
-    // ---- registers of the K step being fetched
-    uint4 xr[4];
-    uint32_t qw[2];
-    auto fetch_main = [&](int64_t k0) {
+    // ---- global fetches (tile indices are clamped by the callers: the loads are unconditional so
+    //      that the compiler waits for them by count, not with vmcnt(0))
+    u32x4 xr[4];
+    auto fetch_x = [&](int tile) {
 #pragma unroll
-        for (int pi = 0; pi < 4; ++pi) xr[pi] = *reinterpret_cast<const uint4*>(x + xm[pi] * K + xc8 * 8 + k0);
-        const int64_t wbase = (k0 >> 5) * BITS;              // the K step's codes start at word (k0 / 32) * BITS
-        qw[0] = wsrc[wbase];
-        qw[1] = BITS == 2 ? 0u : wsrc[wbase + 1];
+        for (int p = 0; p < 4; ++p) xr[p] = *reinterpret_cast<const u32x4*>(xsrc[p] + (int64_t)tile * PBK);
     };
-    auto stage_x = [&](int buf) {
-        uint16_t* xb = xs + buf * PBM * PLD;
-#pragma unroll
-        for (int pi = 0; pi < 4; ++pi)
-            *reinterpret_cast<uint4*>(&xb[(pi * 64 + xr_row) * PLD + xc8 * 8]) = xr[pi];
+    auto fetch_q = [&](uint32_t (&q)[2], int tile) {
+        const int64_t wbase = (int64_t)tile * (2 * BITS);       // the K step's codes start at word tile * 2 * BITS
+        q[0] = wsrc[wbase];
+        q[1] = BITS == 2 ? 0u : wsrc[wbase + 1];
     };
-    // code j (0..15) of the fetched quarter
-    auto code_of = [&](uint32_t lo, uint32_t hi, int j) -> uint32_t {
-        if constexpr (BITS == 4) return __builtin_amdgcn_ubfe(j < 8 ? lo : hi, 4 * (j & 7), 4);
-        else if constexpr (BITS == 2) return __builtin_amdgcn_ubfe(lo, 2 * j, 2);
-        else {
-            const int bit = 3 * j;
-            if (bit + 3 <= 32) return __builtin_amdgcn_ubfe(lo, bit, 3);
-            if (bit >= 32) return __builtin_amdgcn_ubfe(hi, bit - 32, 3);
-            return __builtin_amdgcn_alignbit(hi, lo, bit) & 7u;
-        }
+    // LDS address of the table entry of code j (0..15) of the fetched quarter
+    auto entry_addr = [&](uint32_t lo, uint32_t hi, int j) -> uint32_t {
+        constexpr uint32_t mask = (uint32_t)(L - 1) << 7;
+        const int bit = BITS * j;
+        uint32_t v;
+        if (bit + BITS <= 32) v = bit >= 7 ? lo >> (bit - 7) : lo << (7 - bit);
+        else if (bit >= 32) v = bit - 32 >= 7 ? hi >> (bit - 32 - 7) : hi << (7 - (bit - 32));
+        else v = __builtin_amdgcn_alignbit(hi, lo, bit) << 7;
+        return (v & mask) | tbase;
     };
-    auto stage_w_main = [&](int buf) {
-        uint16_t* wb = ws + buf * PBN * PLD;
-        uint32_t lo = qw[0], hi = qw[1];
+    auto code_words = [&](const uint32_t (&q)[2], uint32_t& lo, uint32_t& hi) {
+        lo = q[0]; hi = q[1];
         if constexpr (BITS == 3) {
             const unsigned long long v = (((unsigned long long)hi << 32) | lo) >> qshift;
             lo = (uint32_t)v; hi = (uint32_t)(v >> 32);
         }
-#pragma unroll
-        for (int hlf = 0; hlf < 2; ++hlf) {
-            uint32_t b[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) b[j] = *reinterpret_cast<lds_u32>(tbase + (code_of(lo, hi, hlf * 8 + j) << 7));
-            *reinterpret_cast<uint4*>(&wb[wrow * PLD + wq * 16 + hlf * 8]) =
-                make_uint4(b[0] | (b[1] << 16), b[2] | (b[3] << 16), b[4] | (b[5] << 16), b[6] | (b[7] << 16));
-        }
     };
-    // matrix cores on buffer `buf`; FIRST: the K step starts a group, its first MFMAs take a zero accumulator
-    auto mma = [&](int buf, auto first) {
-        constexpr bool FIRST = decltype(first)::value;
-        const uint16_t* xb = xs + buf * PBM * PLD;
-        const uint16_t* wb = ws + buf * PBN * PLD;
+
+    // ---- one K step: matrix cores on buffer BUF, staging of the next step into buffer BUF ^ 1.
+    //      FIRST: the step starts a group (its first MFMAs take a zero accumulator); FOLD: it ends
+    //      one (acc += scale * part).  q: the codes of the step being staged; qn / tile_q: the set
+    //      freed by this step's staging is refilled with the codes of step tile_q.
+    auto step = [&](auto buf_, auto first_, auto fold_, uint32_t (&q)[2], int tile_q, int tile_x, uint32_t sraw0, uint32_t sraw1) {
+        constexpr int BUF = decltype(buf_)::value;
+        constexpr bool FIRST = decltype(first_)::value, FOLD = decltype(fold_)::value;
+        bf16x8 a[2][2], b[2][2];
+        uint32_t lk[2][8], wpk[4];
+        uint32_t lo, hi;
+        auto read_ops = [&](int set, int kk) {
 #pragma unroll
-        for (int kk = 0; kk < PBK / 16; ++kk) {
-            const int col = kk * 16 + (lane >> 5) * 8;
+            for (int i = 0; i < 2; ++i) {
+                a[set][i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<lds_u4>(ard + BUF * kXBuf + i * (32 * PLD * 2) + kk * 32));
+                b[set][i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<lds_u4>(brd + BUF * kWBuf + i * (32 * PLD * 2) + kk * 32));
+            }
+        };
+        auto w_issue = [&](int c, int h) {                      // four of the eight lookups of chunk c
+#pragma unroll
+            for (int t = 0; t < 4; ++t) lk[c][h * 4 + t] = *reinterpret_cast<lds_u32>(entry_addr(lo, hi, c * 8 + h * 4 + t));
+        };
+        auto w_finish = [&](int c, int h) {                     // pack half of chunk c; then the 16-byte write
+#pragma unroll
+            for (int t = 0; t < 2; ++t) wpk[h * 2 + t] = lk[c][h * 4 + 2 * t] | (lk[c][h * 4 + 2 * t + 1] << 16);
+            if (h == 1)
+                *reinterpret_cast<lds_u4>(wwr + (BUF ^ 1) * kWBuf + c * 16) = u32x4{wpk[0], wpk[1], wpk[2], wpk[3]};
+        };
+        auto x_write = [&](int p) {
+            *reinterpret_cast<lds_u4>(xwr + (BUF ^ 1) * kXBuf + p * (64 * PLD * 2)) = xr[p];
+        };
+        float s0 = 0.f, s1 = 0.f;
+        auto fold = [&](int t) {
+            const int i = t >> 1, j = t & 1;
+            const float s = j ? s1 : s0;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = __builtin_fmaf(part[i][j][v], s, acc[i][j][v]);
+        };
+
+        read_ops(0, 0);
+        code_words(q, lo, hi);
+        w_issue(0, 0);
+        w_issue(0, 1);
+        ANY4_SB();
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            const int cur = kk & 1;
+            if (kk < 3) read_ops(cur ^ 1, kk + 1);
+            ANY4_SB();
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int i = t >> 1, j = t & 1;
+                part[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cur][i], b[cur][j], (FIRST && kk == 0) ? zero : part[i][j], 0, 0, 0);
+                if (kk == 0) {
+                    if (t < 2) w_finish(0, t);
+                    else w_issue(1, t - 2);
+                } else if (kk == 1) {
+                    if (t < 2) w_finish(1, t);
+                    else if (t == 2) fetch_q(q, tile_q);        // the set is free: its codes are in lo / hi and used up
+                } else if (kk == 2) {
+                    x_write(t);
+                    if (t == 3) fetch_x(tile_x);                // the registers are free again: a full K step of lead
+                } else if (FOLD) {
+                    // the scales were fetched two K steps ago; widening them here, not earlier,
+                    // keeps the wait for that fetch away from the start of the group
+                    if (t == 1) { s0 = bf16_to_f32(sraw0); s1 = bf16_to_f32(sraw1); }
+                    if (t >= 2) fold(t - 2);
+                }
+                ANY4_SB();
+            }
+        }
+        if constexpr (FOLD) { fold(2); fold(3); }
+    };
+    // matrix cores on buffer 0, accumulating straight into acc (the offset steps: nothing to scale)
+    auto mma_plain = [&]() {
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
             bf16x8 a[2], b[2];
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
-                a[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&xb[(wm * 64 + i * 32 + (lane & 31)) * PLD + col]));
-                b[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&wb[(wn * 64 + i * 32 + (lane & 31)) * PLD + col]));
+                a[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<lds_u4>(ard + i * (32 * PLD * 2) + kk * 32));
+                b[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<lds_u4>(brd + i * (32 * PLD * 2) + kk * 32));
             }
 #pragma unroll
             for (int i = 0; i < 2; ++i)
 #pragma unroll
                 for (int j = 0; j < 2; ++j)
-                    part[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], (FIRST && kk == 0) ? zero : part[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
         }
     };
-    auto fold = [&](float s0, float s1) {
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                acc[i][0][v] = __builtin_fmaf(part[i][0][v], s0, acc[i][0][v]);
-                acc[i][1][v] = __builtin_fmaf(part[i][1][v], s1, acc[i][1][v]);
-            }
-    };
-    using T = std::true_type;
-    using F = std::false_type;
+    using B0 = std::integral_constant<int, 0>;
+    using B1 = std::integral_constant<int, 1>;
+    using Yes = std::true_type;
+    using No = std::false_type;
 
-    // ---- main loop over groups of 128 (two K steps each).  While the matrix cores work on one buffer,
-    //      the next K step (fetched before the MFMAs were issued) is looked up and written to the other.
-    fetch_main(0);                                             // in flight while the tables are filled
+    uint32_t q0[2], q1[2];
+    fetch_x(0);                                                // in flight while the tables are filled
+    fetch_q(q0, 0);
+    fetch_q(q1, 1);
     // per-row tables of this block's weight rows (rows past N are clamped: they are never stored):
     // one thread fetches 8 bytes (4 entries) of a row and writes each entry's 4 adjacent copies at once
     {
@@ -211,32 +277,48 @@ __global__ __launch_bounds__(PTHREADS, 1) void prefill_kernel(
             *reinterpret_cast<uint4*>(dst + 96) = make_uint4(e3, e3, e3, e3);
         }
     }
+    lds_barrier();                                             // tables are written
+    // K step 0 goes to buffer 0 with nothing to overlap with
+    {
+#pragma unroll
+        for (int p = 0; p < 4; ++p) *reinterpret_cast<lds_u4>(xwr + p * (64 * PLD * 2)) = xr[p];
+        uint32_t lo, hi;
+        code_words(q0, lo, hi);
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            uint32_t v[8];
+#pragma unroll
+            for (int t = 0; t < 8; ++t) v[t] = *reinterpret_cast<lds_u32>(entry_addr(lo, hi, c * 8 + t));
+            *reinterpret_cast<lds_u4>(wwr + c * 16) =
+                u32x4{v[0] | (v[1] << 16), v[2] | (v[3] << 16), v[4] | (v[5] << 16), v[6] | (v[7] << 16)};
+        }
+        fetch_q(q0, min(2, T - 1));
+        fetch_x(1);
+    }
+    lds_barrier();
 
-    __syncthreads();                                           // tables are written
-    stage_x(0);
-    stage_w_main(0);
-    __syncthreads();
+    // ---- main loop, one group of 128 (two K steps) per iteration.  Step s works on buffer s % 2 and
+    //      stages step s + 1: activations fetched during step s - 1 (right after that step's LDS
+    //      writes freed the registers), codes from set (s + 1) % 2, which it then refills with the
+    //      codes of step s + 3.  The last step stages a repeat of step T - 1 into a buffer that is
+    //      not read again.
     for (int64_t g = 0; g < G; ++g) {
-        const float s0 = bf16_to_f32(scol[0][g]), s1 = bf16_to_f32(scol[1][g]);
-        const bool more = g + 1 < G;
-        fetch_main(g * kGroup + PBK);
-        mma(0, T{});
-        stage_x(1);
-        stage_w_main(1);
-        __syncthreads();
-        if (more) fetch_main((g + 1) * kGroup);
-        mma(1, F{});
-        if (more) { stage_x(0); stage_w_main(0); }
-        fold(s0, s1);
-        __syncthreads();
+        const uint32_t sraw0 = scol[0][g], sraw1 = scol[1][g];
+        const int s = (int)(2 * g);
+        step(B0{}, Yes{}, No{}, q1, min(s + 3, T - 1), min(s + 2, T - 1), 0u, 0u);
+        lds_barrier();
+        step(B1{}, No{}, Yes{}, q0, min(s + 4, T - 1), min(s + 3, T - 1), sraw0, sraw1);
+        lds_barrier();
     }
 
     // ---- offset term: a few more K steps over the group dimension (activation group sums split into
     //      bf16 hi + lo in columns 2g, 2g+1; both columns meet offset[n][g]); unscaled
     for (int64_t k0 = 0; k0 < KP; k0 += PBK) {
 #pragma unroll
-        for (int pi = 0; pi < 4; ++pi)
-            xr[pi] = k0 + xc8 * 8 < KP ? *reinterpret_cast<const uint4*>(xsums + xm[pi] * KP + xc8 * 8 + k0) : make_uint4(0, 0, 0, 0);
+        for (int p = 0; p < 4; ++p) {
+            const uint16_t* src = xsums + min(m0 + p * 64 + xr_row, M - 1) * KP + xc8 * 8 + k0;
+            xr[p] = k0 + xc8 * 8 < KP ? *reinterpret_cast<const u32x4*>(src) : u32x4{0, 0, 0, 0};
+        }
         uint32_t pk[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
@@ -244,13 +326,13 @@ __global__ __launch_bounds__(PTHREADS, 1) void prefill_kernel(
             const uint32_t b = gg < G ? offset[wn_glob * G + gg] : 0u;
             pk[j] = b | (b << 16);
         }
-        stage_x(0);
-        *reinterpret_cast<uint4*>(&ws[wrow * PLD + wq * 16]) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
-        *reinterpret_cast<uint4*>(&ws[wrow * PLD + wq * 16 + 8]) = make_uint4(pk[4], pk[5], pk[6], pk[7]);
-        __syncthreads();
-        mma(0, T{});
-        fold(1.f, 1.f);
-        __syncthreads();
+#pragma unroll
+        for (int p = 0; p < 4; ++p) *reinterpret_cast<lds_u4>(xwr + p * (64 * PLD * 2)) = xr[p];
+        *reinterpret_cast<lds_u4>(wwr) = u32x4{pk[0], pk[1], pk[2], pk[3]};
+        *reinterpret_cast<lds_u4>(wwr + 16) = u32x4{pk[4], pk[5], pk[6], pk[7]};
+        lds_barrier();
+        mma_plain();
+        lds_barrier();
     }
 
     // ---- store: accumulator element v of a lane is row 8*(v/4) + 4*(lane/32) + v%4, column lane%32
@@ -268,7 +350,7 @@ __global__ __launch_bounds__(PTHREADS, 1) void prefill_kernel(
 }
 
 constexpr size_t prefill_lds_bytes(int bits) {
-    return (size_t)(2 * PBM * PLD + 2 * PBN * PLD) * 2 + (size_t)PBN * (1 << bits) * 4 * 4;
+    return (size_t)kTableOff + (size_t)PBN * (1 << bits) * 4 * 4;
 }
 
 size_t prefill_workspace_bytes(int64_t M, int64_t K) {
@@ -282,7 +364,7 @@ hipError_t launch_prefill(const uint16_t* x, const uint32_t* codes, const uint16
     const int64_t gm = (M + PBM - 1) / PBM, gn = (N + PBN - 1) / PBN;
     const int64_t units = M * (K / kGroup);
     const int64_t sblocks = (units * 16 + 255) / 256;
-    if (gm > 0x7FFFFFFF || gn > 65535 || sblocks > 0x7FFFFFFF) return hipErrorInvalidValue;
+    if (gm > 0x7FFFFFFF || gn > 65535 || sblocks > 0x7FFFFFFF || K / kGroup > 0x1FFFFFFF) return hipErrorInvalidValue;
     const int KP = prefill_kp(K);
     uint16_t* xsums = static_cast<uint16_t*>(workspace);
     hipLaunchKernelGGL(group_sums_kernel, dim3((unsigned)sblocks), dim3(256), 0, stream, x, M, K, KP, xsums);
