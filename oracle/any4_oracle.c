@@ -31,6 +31,9 @@
  * (nf4-style) equivalence, closed forms (one-hot table, constant codes, zero
  * table, unit-vector activations), reduction to a library fp64 matmul, pack /
  * unpack round trips, and the bits-per-weight figure printed in section 2.4.1.
+ * The tile-major re-layout (any4o_repack) is pinned by a word-level transpose written
+ * with numpy, by reading single codes back out of it, by its zero padding and by the
+ * multiset of its words.
  */
 #include <math.h>
 #include <stdint.h>
@@ -77,6 +80,41 @@ int any4o_pack(const uint8_t *codes_u8, int64_t N, int64_t K, int bits, uint32_t
                 int64_t b = k * bits + i;
                 if ((c >> i) & 1u) row[b / 32] |= 1u << (b % 32);
             }
+        }
+    }
+    return 0;
+}
+
+/* Tile-major re-layout of the packed codes.  The paper re-arranges the weights offline so
+ * that what one lane loads is already its operand of the matrix instruction (section 4.2,
+ * second paragraph: the data is laid out in the order the tensor-core fragments want and
+ * the kernel loads it without any shuffling).  The layout defined here is that idea for a
+ * 64-lane wavefront whose lane (n, q) works on row n of a tile of 16 rows and on quarter q
+ * of a group of 128 codes:
+ *   rows form tiles of 16 (the last tile is padded with rows of zero codes);
+ *   the codes of (tile t, group g) are one unit of 64 pieces, units in order (t, g);
+ *   piece 16 * q + n of a unit holds codes 32 q .. 32 q + 31 of group g of row 16 t + n,
+ *   as a little-endian bit stream of 32 * bits bits, first code in the lowest bits.
+ * Written code by code, bit by bit.  Returns 0, or -1 on bad arguments. */
+int64_t any4o_repack_words(int64_t N, int64_t K, int bits) {
+    if (N < 1 || K < 1 || K % ANY4O_GROUP || !bits_ok(bits)) return -1;
+    return (N + 15) / 16 * 16 * any4o_row_words(K, bits);
+}
+
+int any4o_repack(const uint32_t *packed, int64_t N, int64_t K, int bits, uint32_t *out) {
+    int64_t total = any4o_repack_words(N, K, bits);
+    if (!packed || !out || total < 0) return -1;
+    int64_t W = any4o_row_words(K, bits), G = K / ANY4O_GROUP;
+    memset(out, 0, (size_t)total * sizeof(uint32_t));
+    for (int64_t r = 0; r < N; ++r) {
+        int64_t t = r / 16, n = r % 16;
+        for (int64_t k = 0; k < K; ++k) {
+            uint32_t c = any4o_code(packed + r * W, k, bits);
+            int64_t g = k / ANY4O_GROUP, q = (k % ANY4O_GROUP) / 32, e = k % 32;
+            int64_t piece = (t * G + g) * 64 + 16 * q + n;
+            int64_t b0 = piece * 32 * bits + e * bits;       /* bit position in the whole buffer */
+            for (int i = 0; i < bits; ++i)
+                if ((c >> i) & 1u) out[(b0 + i) / 32] |= 1u << ((b0 + i) % 32);
         }
     }
     return 0;

@@ -38,6 +38,10 @@ def _load():
         lib.any4o_code.argtypes = [p, i64, ctypes.c_int]
         lib.any4o_pack.restype = ctypes.c_int
         lib.any4o_pack.argtypes = [p, i64, i64, ctypes.c_int, p]
+        lib.any4o_repack_words.restype = i64
+        lib.any4o_repack_words.argtypes = [i64, i64, ctypes.c_int]
+        lib.any4o_repack.restype = ctypes.c_int
+        lib.any4o_repack.argtypes = [p, i64, i64, ctypes.c_int, p]
         lib.any4o_dequant.restype = i64
         lib.any4o_dequant.argtypes = [p, p, p, p, i64, i64, ctypes.c_int, p]
         lib.any4o_gemm.restype = ctypes.c_int
@@ -67,6 +71,19 @@ def pack(codes_u8: np.ndarray, bits: int) -> np.ndarray:
     rc = _load().any4o_pack(psrc, N, K, bits, out.ctypes.data_as(ctypes.c_void_p))
     if rc != 0:
         raise ValueError(f"any4o_pack failed with {rc}")
+    return out
+
+
+def repack(packed: np.ndarray, K: int, bits: int) -> np.ndarray:
+    """uint32 [N, K*bits/32] -> the tile-major layout, uint32 [ceil(N/16)*16 * K*bits/32]."""
+    N = packed.shape[0]
+    a, pa = _c(packed, np.uint32)
+    words = int(_load().any4o_repack_words(N, K, bits))
+    if words < 0:
+        raise ValueError("any4o_repack_words: bad arguments")
+    out = np.empty(words, dtype=np.uint32)
+    if _load().any4o_repack(pa, N, K, bits, out.ctypes.data_as(ctypes.c_void_p)) != 0:
+        raise ValueError("any4o_repack: bad arguments")
     return out
 
 
