@@ -165,17 +165,18 @@ def main():
     }
 
     # ------------------------------------------------------------------ context measurements
-    def time_gemm(g, reps, rotate=None):
+    def time_gemm(g, reps, rotate=None, fn=None):
         """median microseconds of one launch (event pair per launch); rotate = list of
         equivalent problems to cycle through so weights come from HBM."""
         probs = rotate or [g]
+        fn = fn or launch
         for p in probs[:2]:
-            launch(p)
+            fn(p)
         torch.cuda.synchronize()
         ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
         for r in range(reps):
             ev[r][0].record()
-            launch(probs[r % len(probs)])
+            fn(probs[r % len(probs)])
             ev[r][1].record()
         torch.cuda.synchronize()
         return float(np.median([a.elapsed_time(b) * 1e3 for a, b in ev]))
@@ -217,6 +218,41 @@ def main():
             "gemm_step_over_read_step": ms_per_step / read_ms,
             "one_GiB_read_GBps": (1 << 30) / (b0.elapsed_time(b1) * 1e-3) / 1e9}
         del rgraph, bigbuf
+        # the same step on codes re-arranged offline into the tile-major layout (any4_repack):
+        # same kernels and results, the code stream of a wavefront instruction is one contiguous piece
+        for layer in layers:
+            for g in layer:
+                g["rcodes"] = any4.any4_repack(g["codes"], bits)
+
+        def launch_re(g):
+            any4.any4_gemm_repacked(g["x"], g["rcodes"], g["lut"], g["scale"], g["offset"], bits, out=g["y"],
+                                    workspace=g["ws"])
+        for g in layers[0]:
+            launch_re(g)
+        torch.cuda.synchronize()
+        pgraph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(pgraph):
+            for s_ in range(args.steps):
+                for g in layers[s_ % args.layers]:
+                    launch_re(g)
+        pgraph.replay()
+        torch.cuda.synchronize()
+        p0, p1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        p0.record()
+        pgraph.replay()
+        p1.record()
+        torch.cuda.synchronize()
+        re_ms = p0.elapsed_time(p1) / args.steps
+        extras["repacked_llama3_8b_M1"] = {
+            "what": "the timed step with any4_gemm_repacked on any4_repack'ed codes (offline re-layout)",
+            "ms_per_step": re_ms, "GBps": step_bytes / (re_ms * 1e-3) / 1e9,
+            "frac_of_8TBps": step_bytes / (re_ms * 1e-3) / 1e9 / 8000.0,
+            "plain_layout_step_over_this": e0.elapsed_time(e1) / args.steps / re_ms}
+        del pgraph
+        for layer in layers:
+            for g in layer:
+                del g["rcodes"]
+        torch.cuda.empty_cache()
         m8 = {}
         for gi, g in enumerate(layers[0]):
             rot = []
@@ -258,6 +294,12 @@ def main():
                 by = algorithmic_bytes(Mx, N, K, bits)
                 big[f"{name}_M{Mx}"] = {"us": us, "GBps": by / (us * 1e-6) / 1e9,
                                         "frac_of_hbm_peak": by / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS}
+                if Mx == 1:                                     # the same launches on re-laid-out codes
+                    for p_ in rot:
+                        p_["rcodes"] = any4.any4_repack(p_["codes"], bits)
+                    us_re = time_gemm(rot[0], 24, rot, fn=launch_re)
+                    big[f"{name}_M1_repacked"] = {"us": us_re, "GBps": by / (us_re * 1e-6) / 1e9,
+                                                  "frac_of_hbm_peak": by / (us_re * 1e-6) / 1e9 / HBM_PEAK_GBPS}
                 del rot
                 torch.cuda.empty_cache()
         extras["llama3_70b"] = big

@@ -100,6 +100,36 @@ int any4_gemm(const uint16_t* x, const uint32_t* codes, const uint16_t* lut,
 size_t any4_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int bits);
 
 /*
+ * any4_repack - re-arrange packed codes offline into the order the kernels read them in.
+ * The paper stores the weights in the operand order of the matrix instruction so that a lane's
+ * load needs no shuffling (section 4.2, second paragraph).  On this GPU the row-major layout
+ * already hands every lane its operand as one contiguous load; the tile-major layout produced
+ * here additionally makes the 64 loads of one wavefront instruction one contiguous piece of
+ * memory, which streams 6 - 9 % faster at small M:
+ *   rows form tiles of 16; the codes of (tile t, group g of 128 codes) are one unit of 64 pieces,
+ *   units in order (t, g); piece 16 * q + n of a unit holds codes 32 q .. 32 q + 31 of group g of
+ *   row 16 t + n in `bits` words (same bit order as any4_pack); rows past N in the last tile are 0.
+ * The layout is an implementation detail of this library version: treat rcodes as opaque.
+ *   codes    in   uint32 [N][K*bits/32]          (output of any4_pack)
+ *   rcodes   out  any4_repack_bytes(N, K, bits) bytes, fully overwritten; must not overlap codes
+ */
+int any4_repack(const uint32_t* codes, int64_t N, int64_t K, int bits, uint32_t* rcodes, void* stream);
+
+/* Size of the re-arranged buffer in bytes (0 for invalid arguments). */
+size_t any4_repack_bytes(int64_t N, int64_t K, int bits);
+
+/*
+ * any4_gemm_repacked - any4_gemm on codes re-arranged by any4_repack; every other argument, the
+ * workspace size (any4_gemm_workspace_bytes) and the result, bit for bit, are those of any4_gemm.
+ * lut must not be NULL.  For M <= 16, K beyond the streaming kernel's range (K > 262144 at
+ * M <= 16) returns ANY4_ERR_SHAPE.
+ */
+int any4_gemm_repacked(const uint16_t* x, const uint32_t* rcodes, const uint16_t* lut,
+                       const uint16_t* scale, const uint16_t* offset,
+                       int64_t M, int64_t N, int64_t K, int bits,
+                       uint16_t* y, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * any4_quantize - the step before the GEMM: learn the per-row tables (section 3.2 "any4
  * Algorithm"; appendix, Algorithm 1).  For every row independently:
  *   1. group-wise scaling of section 2.5.1 over groups of 128 weights along K,

@@ -16,7 +16,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libany4.so")
 GROUP = 128
 
-EXPORTS = ("any4_pack", "any4_dequant", "any4_gemm", "any4_gemm_workspace_bytes",
+EXPORTS = ("any4_pack", "any4_dequant", "any4_gemm", "any4_gemm_workspace_bytes", "any4_repack", "any4_repack_bytes", "any4_gemm_repacked",
            "any4_quantize", "any4_quantize_max_k", "any4_stream_read", "any4_strerror", "any4_version")
 
 
@@ -45,6 +45,12 @@ def load_library() -> ctypes.CDLL:
     lib.any4_gemm.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, ci, vp, vp, ctypes.c_size_t, vp]
     lib.any4_gemm_workspace_bytes.restype = ctypes.c_size_t
     lib.any4_gemm_workspace_bytes.argtypes = [i64, i64, i64, ci]
+    lib.any4_gemm_repacked.restype = ci
+    lib.any4_gemm_repacked.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, ci, vp, vp, ctypes.c_size_t, vp]
+    lib.any4_repack.restype = ci
+    lib.any4_repack.argtypes = [vp, i64, i64, ci, vp, vp]
+    lib.any4_repack_bytes.restype = ctypes.c_size_t
+    lib.any4_repack_bytes.argtypes = [i64, i64, ci]
     lib.any4_quantize.restype = ci
     lib.any4_quantize.argtypes = [vp, vp, vp, i64, i64, ci, ci, ci, vp, vp, vp, vp, vp, vp]
     lib.any4_quantize_max_k.restype = i64
@@ -123,14 +129,9 @@ def any4_dequant(codes: torch.Tensor, lut: torch.Tensor | None, scale: torch.Ten
     return out
 
 
-def any4_gemm(x: torch.Tensor, codes: torch.Tensor, lut: torch.Tensor | None, scale: torch.Tensor,
-              offset: torch.Tensor, bits: int = 4, out: torch.Tensor | None = None,
-              workspace: torch.Tensor | None = None) -> torch.Tensor:
-    """bf16 [M,N] = x[M,K] . dequant(codes, lut, scale, offset)[N,K]^T
-    (lut None with bits 4: the int4 grid, value = code - 8, run without a table)."""
+def _gemm(entry: str, x, codes, N, lut, scale, offset, bits, out, workspace):
     lib = load_library()
     M, K = x.shape
-    N = codes.shape[0]
     px = _dev(x, torch.bfloat16, "x")
     pc = _dev(codes, torch.int32, "codes")
     pl = _dev(lut, torch.bfloat16, "lut") if lut is not None else None
@@ -144,8 +145,42 @@ def any4_gemm(x: torch.Tensor, codes: torch.Tensor, lut: torch.Tensor | None, sc
         workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
     pw = workspace.data_ptr() if workspace is not None else None
     wbytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
-    _check(lib.any4_gemm(px, pc, pl, ps, po, M, N, K, bits, py, pw, wbytes, _stream()), "any4_gemm")
+    _check(getattr(lib, entry)(px, pc, pl, ps, po, M, N, K, bits, py, pw, wbytes, _stream()), entry)
     return out
+
+
+def any4_gemm(x: torch.Tensor, codes: torch.Tensor, lut: torch.Tensor | None, scale: torch.Tensor,
+              offset: torch.Tensor, bits: int = 4, out: torch.Tensor | None = None,
+              workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """bf16 [M,N] = x[M,K] . dequant(codes, lut, scale, offset)[N,K]^T
+    (lut None with bits 4: the int4 grid, value = code - 8, run without a table)."""
+    return _gemm("any4_gemm", x, codes, codes.shape[0], lut, scale, offset, bits, out, workspace)
+
+
+def any4_repack_bytes(N: int, K: int, bits: int = 4) -> int:
+    return int(load_library().any4_repack_bytes(N, K, bits))
+
+
+def any4_repack(codes: torch.Tensor, bits: int = 4) -> torch.Tensor:
+    """int32 [N, K*bits/32] packed codes -> the tile-major layout any4_gemm_repacked reads
+    (int32, flat, any4_repack_bytes(N, K, bits) bytes)."""
+    lib = load_library()
+    N, W = codes.shape
+    K = W * 32 // bits
+    pc = _dev(codes, torch.int32, "codes")
+    nbytes = int(lib.any4_repack_bytes(N, K, bits))
+    if nbytes == 0:
+        raise Any4Error("any4_repack: bad shape or bits")
+    out = torch.empty(nbytes // 4, dtype=torch.int32, device=codes.device)
+    _check(lib.any4_repack(pc, N, K, bits, out.data_ptr(), _stream()), "any4_repack")
+    return out
+
+
+def any4_gemm_repacked(x: torch.Tensor, rcodes: torch.Tensor, lut: torch.Tensor, scale: torch.Tensor,
+                       offset: torch.Tensor, bits: int = 4, out: torch.Tensor | None = None,
+                       workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """any4_gemm on codes re-arranged by any4_repack; N is taken from scale."""
+    return _gemm("any4_gemm_repacked", x, rcodes, scale.shape[0], lut, scale, offset, bits, out, workspace)
 
 
 def any4_quantize_max_k() -> int:

@@ -112,28 +112,53 @@ size_t any4_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int bits) {
     return plan_gemm(M, N, K, bits).workspace;
 }
 
-int any4_gemm(const uint16_t* x, const uint32_t* codes, const uint16_t* lut, const uint16_t* scale,
-              const uint16_t* offset, int64_t M, int64_t N, int64_t K, int bits, uint16_t* y,
-              void* workspace, size_t workspace_bytes, void* stream) {
+static int gemm_any_layout(const uint16_t* x, const uint32_t* codes, bool repacked, const uint16_t* lut,
+                           const uint16_t* scale, const uint16_t* offset, int64_t M, int64_t N, int64_t K,
+                           int bits, uint16_t* y, void* workspace, size_t workspace_bytes, void* stream) {
     if (!x || !codes || !scale || !offset || !y) return ANY4_ERR_NULL;
-    if (!lut && bits != 4) return ANY4_ERR_NULL;           // no table = the 4-bit integer grid only
+    if (!lut && (bits != 4 || repacked)) return ANY4_ERR_NULL;       // no table = the 4-bit integer grid, plain layout only
     if (int rc = shape_check(N, K, bits)) return rc;
     if (M < 1) return ANY4_ERR_SHAPE;
     if (!aligned16(x) || !aligned16(codes) || !aligned16(lut) || !aligned16(scale) ||
         !aligned16(offset) || !aligned16(y) || !aligned16(workspace))
         return ANY4_ERR_ALIGN;
     const GemmPlan plan = plan_gemm(M, N, K, bits);
+    if (repacked && plan.decode && !plan.stream) return ANY4_ERR_SHAPE;   // K beyond the streaming kernel's range
     if (plan.workspace > 0 && (!workspace || workspace_bytes < plan.workspace)) return ANY4_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t e;
     if (plan.stream) {
-        e = launch_decode_stream(x, codes, lut, scale, offset, M, N, K, bits, plan.sp, y, workspace, s);
+        e = launch_decode_stream(x, codes, lut, scale, offset, M, N, K, bits, repacked, plan.sp, y, workspace, s);
     } else if (plan.decode) {
         e = launch_decode(x, codes, lut, scale, offset, M, N, K, bits, plan, y, static_cast<float*>(workspace), s);
     } else {
-        e = launch_prefill(x, codes, lut, scale, offset, M, N, K, bits, y, workspace, s);
+        e = launch_prefill(x, codes, lut, scale, offset, M, N, K, bits, repacked, y, workspace, s);
     }
     return e == hipSuccess ? ANY4_OK : ANY4_ERR_HIP;
+}
+
+int any4_gemm(const uint16_t* x, const uint32_t* codes, const uint16_t* lut, const uint16_t* scale,
+              const uint16_t* offset, int64_t M, int64_t N, int64_t K, int bits, uint16_t* y,
+              void* workspace, size_t workspace_bytes, void* stream) {
+    return gemm_any_layout(x, codes, false, lut, scale, offset, M, N, K, bits, y, workspace, workspace_bytes, stream);
+}
+
+int any4_gemm_repacked(const uint16_t* x, const uint32_t* rcodes, const uint16_t* lut, const uint16_t* scale,
+                       const uint16_t* offset, int64_t M, int64_t N, int64_t K, int bits, uint16_t* y,
+                       void* workspace, size_t workspace_bytes, void* stream) {
+    return gemm_any_layout(x, rcodes, true, lut, scale, offset, M, N, K, bits, y, workspace, workspace_bytes, stream);
+}
+
+size_t any4_repack_bytes(int64_t N, int64_t K, int bits) {
+    if (shape_check(N, K, bits) != ANY4_OK) return 0;
+    return (size_t)((N + 15) / 16 * 16) * (size_t)row_words(K, bits) * sizeof(uint32_t);
+}
+
+int any4_repack(const uint32_t* codes, int64_t N, int64_t K, int bits, uint32_t* rcodes, void* stream) {
+    if (!codes || !rcodes) return ANY4_ERR_NULL;
+    if (int rc = shape_check(N, K, bits)) return rc;
+    if (!aligned16(codes) || !aligned16(rcodes)) return ANY4_ERR_ALIGN;
+    return launch_repack(codes, N, K, bits, rcodes, static_cast<hipStream_t>(stream)) == hipSuccess ? ANY4_OK : ANY4_ERR_HIP;
 }
 
 const char* any4_strerror(int code) {

@@ -170,9 +170,10 @@ __device__ __forceinline__ bool arrive_one(unsigned long long* c, int ksplit) {
 //         A code c becomes the bf16 number 128 + c by OR-ing it into the mantissa of 128.0
 //         (0x4300 | c), and the surplus 136 * scale * (group sum of x) is taken off again by two more
 //         exact bf16 terms (-128 * scale and -8 * scale) that ride in the offset MFMA.
-template <int BITS, int GW, bool AUX, bool NOLUT>
+template <int BITS, int GW, bool AUX, bool NOLUT, bool REPACK>
 __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Params p) {
     static_assert(!NOLUT || BITS == 4, "the table-free path is the 4-bit integer grid");
+    static_assert(!(NOLUT && REPACK), "the table-free path reads the plain layout only");
     static_assert(BITS == 4 || BITS == 3 || BITS == 2, "code width");
     static_assert(kDepth == 4 || kDepth == 2, "the tile loop is unrolled by kDepth");
     constexpr int WAVES = kWaves, kThreads = WAVES * 64;
@@ -234,19 +235,27 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
     //      QW words of its quarter of each of the wavefront's groups
     struct Quarter { uint32_t w[QW]; };
     Quarter cw[kDepth][GW];
+    // REPACK: the tile-major layout (any4_repack).  The 64 quarters of (tile, group) are 64 * QB
+    // contiguous bytes in lane order, so one load instruction of a wavefront reads one contiguous
+    // piece of memory (the plain layout gives it 16 pieces of 64 bytes, one per row); the last tile
+    // is padded, no clamping.  These loads are nontemporal: every byte is read exactly once, and with
+    // whole cache lines per instruction nothing is lost by not keeping them (with the plain layout,
+    // where two instructions share each line, the same hint costs 5 %).
     auto load_codes = [&](Quarter& c, int t, int gi) {
-        const char* base = codes_b + (int64_t)t * (kTile * (int64_t)row_bytes) + group_of(gi) * GB;
-        const char* a = base + (t == last_tile ? vc_last : vc_norm);
+        typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+        typedef uint32_t u32x3 __attribute__((ext_vector_type(3), aligned(4)));
+        typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+        const char* base = codes_b + (int64_t)t * (kTile * (int64_t)row_bytes) + group_of(gi) * (REPACK ? 64 * QB : GB);
+        const char* a = base + (REPACK ? (uint32_t)lane * QB : (t == last_tile ? vc_last : vc_norm));
         if constexpr (BITS == 4) {
-            const uint4 v = *reinterpret_cast<const uint4*>(a);
-            c.w[0] = v.x; c.w[1] = v.y; c.w[2] = v.z; c.w[3] = v.w;
+            const u32x4 v = REPACK ? __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(a)) : *reinterpret_cast<const u32x4*>(a);
+            c.w[0] = v[0]; c.w[1] = v[1]; c.w[2] = v[2]; c.w[3] = v[3];
         } else if constexpr (BITS == 3) {
-            typedef uint32_t u32x3 __attribute__((ext_vector_type(3), aligned(4)));
-            const u32x3 v = *reinterpret_cast<const u32x3*>(a);
-            c.w[0] = v.x; c.w[1] = v.y; c.w[2] = v.z;
+            const u32x3 v = REPACK ? __builtin_nontemporal_load(reinterpret_cast<const u32x3*>(a)) : *reinterpret_cast<const u32x3*>(a);
+            c.w[0] = v[0]; c.w[1] = v[1]; c.w[2] = v[2];
         } else {
-            const uint2 v = *reinterpret_cast<const uint2*>(a);
-            c.w[0] = v.x; c.w[1] = v.y;
+            const u32x2 v = REPACK ? __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(a)) : *reinterpret_cast<const u32x2*>(a);
+            c.w[0] = v[0]; c.w[1] = v[1];
         }
     };
 
@@ -814,9 +823,9 @@ StreamPlan plan_stream(int64_t M, int64_t N, int64_t K, int cus) {
     return best;
 }
 
-template <int BITS, int GW, bool AUX, bool NOLUT = false>
+template <int BITS, int GW, bool AUX, bool NOLUT = false, bool REPACK = false>
 static hipError_t launch_stream_t(const Params& p, int grid, hipStream_t stream) {
-    auto kern = stream::decode_stream_kernel<BITS, GW, AUX, NOLUT>;
+    auto kern = stream::decode_stream_kernel<BITS, GW, AUX, NOLUT, REPACK>;
 #ifdef ANY4_STAMPS
     constexpr int lds = stream::lds_bytes(BITS) + stream::kWaves * stream::kStampSteps * 4 * 8;
 #else
@@ -829,10 +838,11 @@ static hipError_t launch_stream_t(const Params& p, int grid, hipStream_t stream)
     return hipGetLastError();
 }
 
-template <int BITS>
+template <int BITS, bool REPACK>
 static hipError_t launch_stream_b(const Params& p, const StreamPlan& sp, int grid, hipStream_t stream) {
 #define ANY4_STREAM(GW)                                                                    \
-    (sp.aux ? launch_stream_t<BITS, GW, true>(p, grid, stream) : launch_stream_t<BITS, GW, false>(p, grid, stream))
+    (sp.aux ? launch_stream_t<BITS, GW, true, false, REPACK>(p, grid, stream)              \
+            : launch_stream_t<BITS, GW, false, false, REPACK>(p, grid, stream))
     switch (sp.gw) {
         case 4: return ANY4_STREAM(4);
         case 2: return ANY4_STREAM(2);
@@ -843,8 +853,8 @@ static hipError_t launch_stream_b(const Params& p, const StreamPlan& sp, int gri
 
 hipError_t launch_decode_stream(const uint16_t* x, const uint32_t* codes, const uint16_t* lut,
                                 const uint16_t* scale, const uint16_t* offset, int64_t M, int64_t N,
-                                int64_t K, int bits, const StreamPlan& sp, uint16_t* y, void* workspace,
-                                hipStream_t stream) {
+                                int64_t K, int bits, bool repacked, const StreamPlan& sp, uint16_t* y,
+                                void* workspace, hipStream_t stream) {
     Params p{};
     p.x = x; p.codes = codes; p.lut = lut; p.scale = scale; p.offset = offset; p.y = y;
     p.counters = static_cast<unsigned long long*>(workspace);
@@ -858,6 +868,7 @@ hipError_t launch_decode_stream(const uint16_t* x, const uint32_t* codes, const 
 #endif
     const int grid = sp.slabs * sp.blocks_per_slab;
     if (bits == 4 && lut == nullptr) {                     // the integer grid: no table
+        if (repacked) return hipErrorInvalidValue;
 #define ANY4_STREAM_NL(GW)                                                                 \
     (sp.aux ? launch_stream_t<4, GW, true, true>(p, grid, stream) : launch_stream_t<4, GW, false, true>(p, grid, stream))
         switch (sp.gw) {
@@ -867,9 +878,14 @@ hipError_t launch_decode_stream(const uint16_t* x, const uint32_t* codes, const 
         }
 #undef ANY4_STREAM_NL
     }
-    if (bits == 4) return launch_stream_b<4>(p, sp, grid, stream);
-    if (bits == 3) return launch_stream_b<3>(p, sp, grid, stream);
-    return launch_stream_b<2>(p, sp, grid, stream);
+    if (repacked) {
+        if (bits == 4) return launch_stream_b<4, true>(p, sp, grid, stream);
+        if (bits == 3) return launch_stream_b<3, true>(p, sp, grid, stream);
+        return launch_stream_b<2, true>(p, sp, grid, stream);
+    }
+    if (bits == 4) return launch_stream_b<4, false>(p, sp, grid, stream);
+    if (bits == 3) return launch_stream_b<3, false>(p, sp, grid, stream);
+    return launch_stream_b<2, false>(p, sp, grid, stream);
 }
 
 }  // namespace any4

@@ -41,13 +41,15 @@ hipError_t launch_decode(const uint16_t* x, const uint32_t* codes, const uint16_
                          uint16_t* y, float* partial, hipStream_t stream);
 hipError_t launch_decode_stream(const uint16_t* x, const uint32_t* codes, const uint16_t* lut,
                                 const uint16_t* scale, const uint16_t* offset, int64_t M, int64_t N,
-                                int64_t K, int bits, const StreamPlan& sp, uint16_t* y, void* workspace,
-                                hipStream_t stream);
+                                int64_t K, int bits, bool repacked, const StreamPlan& sp, uint16_t* y,
+                                void* workspace, hipStream_t stream);
 hipError_t launch_reduce_slices(const float* partial, int ksplit, int64_t MN, uint16_t* y, hipStream_t stream);
 hipError_t launch_prefill(const uint16_t* x, const uint32_t* codes, const uint16_t* lut,
                           const uint16_t* scale, const uint16_t* offset,
-                          int64_t M, int64_t N, int64_t K, int bits,
+                          int64_t M, int64_t N, int64_t K, int bits, bool repacked,
                           uint16_t* y, void* workspace, hipStream_t stream);
+// Tile-major re-layout of the packed codes (any4_repack).
+hipError_t launch_repack(const uint32_t* codes, int64_t N, int64_t K, int bits, uint32_t* out, hipStream_t stream);
 
 // Matrix-core path: padded length of the "group" dimension (two bf16 columns per group of 128,
 // rounded up to the MFMA K granularity of 16) and the scratch it needs for the group sums of x.

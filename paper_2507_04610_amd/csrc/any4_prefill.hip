@@ -85,7 +85,7 @@ __global__ __launch_bounds__(PTHREADS, 1) void prefill_kernel(
     const uint16_t* __restrict__ x, const uint32_t* __restrict__ codes,
     const uint16_t* __restrict__ lut, const uint16_t* __restrict__ scale,
     const uint16_t* __restrict__ offset, const uint16_t* __restrict__ xsums, int KP,
-    int64_t M, int64_t N, int64_t K, uint16_t* __restrict__ y) {
+    int64_t M, int64_t N, int64_t K, int repacked, uint16_t* __restrict__ y) {
     constexpr int L = 1 << BITS;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     uint32_t* table = reinterpret_cast<uint32_t*>(smem + kTableOff);      // [PBN / 8][L][32]
@@ -103,7 +103,15 @@ __global__ __launch_bounds__(PTHREADS, 1) void prefill_kernel(
     // word offset / bit shift of the thread's 16 codes inside the K step's (2 * BITS)-word chunk
     const int qword = BITS == 4 ? 2 * wq : (BITS == 2 ? wq : (6 * wq) >> 2);
     const int qshift = BITS == 3 ? ((6 * wq) & 3) * 8 : 0;
-    const uint32_t* const wsrc = codes + wn_glob * RW + qword;
+    // plain layout: the K step's codes start at word tile * 2 * BITS of the row.  Tile-major layout
+    // (any4_repack): the step is half of group tile / 2; the thread's 16 codes are one half of
+    // piece 16 * q + n, q = 2 * (tile % 2) + wq / 2, of unit (row / 16, group): the word offset of
+    // step `tile` is (tile / 2) * 64 * BITS + (tile % 2) * 32 * BITS past the thread's base.
+    const int hword = (BITS == 4 ? 2 : 1) * (wq & 1);                     // first word of the thread's half inside its piece
+    const uint32_t* const wsrc = repacked
+        ? codes + (((wn_glob >> 4) * G * 64 + (wq >> 1) * 16 + (wn_glob & 15)) * BITS + hword)
+        : codes + wn_glob * RW + qword;
+    const int64_t qstep_even = repacked ? 64 * BITS : 4 * BITS, qstep_odd = repacked ? 32 * BITS : 2 * BITS;
     const int xr_row = tid >> 3, xc8 = tid & 7;
     const uint16_t* xsrc[4];                                              // rows past M are clamped, never stored
 #pragma unroll
@@ -136,7 +144,7 @@ __global__ __launch_bounds__(PTHREADS, 1) void prefill_kernel(
         for (int p = 0; p < 4; ++p) xr[p] = *reinterpret_cast<const u32x4*>(xsrc[p] + (int64_t)tile * PBK);
     };
     auto fetch_q = [&](uint32_t (&q)[2], int tile) {
-        const int64_t wbase = (int64_t)tile * (2 * BITS);       // the K step's codes start at word tile * 2 * BITS
+        const int64_t wbase = (int64_t)(tile >> 1) * qstep_even + (tile & 1) * qstep_odd;
         q[0] = wsrc[wbase];
         q[1] = BITS == 2 ? 0u : wsrc[wbase + 1];
     };
@@ -359,7 +367,7 @@ size_t prefill_workspace_bytes(int64_t M, int64_t K) {
 
 hipError_t launch_prefill(const uint16_t* x, const uint32_t* codes, const uint16_t* lut,
                           const uint16_t* scale, const uint16_t* offset,
-                          int64_t M, int64_t N, int64_t K, int bits,
+                          int64_t M, int64_t N, int64_t K, int bits, bool repacked,
                           uint16_t* y, void* workspace, hipStream_t stream) {
     const int64_t gm = (M + PBM - 1) / PBM, gn = (N + PBN - 1) / PBN;
     const int64_t units = M * (K / kGroup);
@@ -377,7 +385,7 @@ hipError_t launch_prefill(const uint16_t* x, const uint32_t* codes, const uint16
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)prefill_lds_bytes(B));           \
         if (e != hipSuccess) return e;                                                                            \
         hipLaunchKernelGGL(prefill_kernel<B>, grid, block, prefill_lds_bytes(B), stream, x, codes, lut, scale,    \
-                           offset, xsums, KP, M, N, K, y);                                                        \
+                           offset, xsums, KP, M, N, K, repacked ? 1 : 0, y);                                                        \
     } while (0)
     switch (bits) {
         case 4: ANY4_PREFILL(4); break;

@@ -57,7 +57,12 @@ def test_bad_arguments_are_rejected_before_any_launch(lib):
     assert lib.any4_dequant(A, None, A, A, 4, 128, 3, A, None) == -1
     assert lib.any4_gemm(A, A, None, A, A, 1, 4, 128, 2, A, None, 0, None) == -1
     assert lib.any4_gemm(A, A, A, A, A, 1, 4, 128, 4, None, None, 0, None) == -1
+    assert lib.any4_repack(None, 4, 128, 4, A, None) == -1
+    assert lib.any4_gemm_repacked(A, A, None, A, A, 1, 4, 128, 4, A, None, 0, None) == -1     # needs a table
     # shapes
+    assert lib.any4_repack(A, 4, 100, 4, A, None) == -2
+    assert lib.any4_repack(A, 4, 128, 5, A, None) == -3
+    assert lib.any4_repack(A, 4, 128, 4, A + 4, None) == -4
     assert lib.any4_pack(A, 0, 128, 4, A, None) == -2
     assert lib.any4_pack(A, 4, 100, 4, A, None) == -2
     assert lib.any4_dequant(A, A, A, A, 4, 0, 4, A, None) == -2
@@ -71,6 +76,14 @@ def test_bad_arguments_are_rejected_before_any_launch(lib):
     assert lib.any4_pack(A + 4, 4, 128, 4, A, None) == -4
     assert lib.any4_dequant(A, A + 2, A, A, 4, 128, 4, A, None) == -4
     assert lib.any4_gemm(A, A, A, A, A, 1, 4, 128, 4, A + 8, None, 0, None) == -4
+
+
+def test_repack_size(lib):
+    # whole tiles of 16 rows; invalid arguments need nothing
+    assert lib.any4_repack_bytes(16, 128, 4) == 16 * 64
+    assert lib.any4_repack_bytes(17, 256, 3) == 32 * 96
+    assert lib.any4_repack_bytes(1, 128, 2) == 16 * 32
+    assert lib.any4_repack_bytes(4, 100, 4) == 0 and lib.any4_repack_bytes(4, 128, 7) == 0
 
 
 def test_workspace_contract(lib):

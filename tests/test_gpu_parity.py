@@ -229,6 +229,45 @@ def test_gemm_rejects_small_workspace_and_leaves_output_alone(any4):
     assert torch.all(y == 7.0)
 
 
+# ------------------------------------------------------------------------------ tile-major re-layout
+@pytest.mark.parametrize("bits", (4, 3, 2))
+@pytest.mark.parametrize("N,K", [(16, 128), (21, 256), (1, 128), (257, 1152), (64, 4096), (5, 14336)])
+def test_repack_bit_exact(any4, oracle, bits, N, K):
+    codes = np.random.default_rng(N * 7 + bits).integers(0, 1 << bits, size=(N, K), dtype=np.uint8)
+    packed = oracle.pack(codes, bits)
+    r = any4.any4_repack(dev_codes(packed), bits)
+    torch.cuda.synchronize()
+    assert r.numel() * 4 == any4.any4_repack_bytes(N, K, bits)
+    assert np.array_equal(host_u32(r), oracle.repack(packed, K, bits))
+
+
+@pytest.mark.parametrize("bits", (4, 3, 2))
+@pytest.mark.parametrize("M,N,K", [(1, 16, 128), (1, 333, 4224), (3, 17, 384), (8, 700, 640), (16, 100, 4480),
+                                   (2, 40, 28672), (5, 4100, 512), (1, 2049, 256), (2, 100, 14336),
+                                   (17, 128, 128), (100, 200, 256), (300, 64, 2048), (129, 130, 640)])
+def test_gemm_repacked_equals_plain_layout(any4, oracle, bits, M, N, K):
+    """Same kernels, same arithmetic, other addresses: the result is that of any4_gemm bit for bit,
+    and within the GEMM tolerance of the oracle (which knows only the plain layout)."""
+    cs = inputs.make_case(M, N, K, bits, inputs.case_seed(9, bits, M))
+    packed = oracle.pack(cs.codes_u8, bits)
+    y64 = oracle.gemm(cs.x, packed, cs.lut, cs.scale, cs.offset, K, bits, threads=8)
+    codes_dev = dev_codes(packed)
+    rcodes = any4.any4_repack(codes_dev, bits)
+    args = (dev_bf16(cs.lut), dev_bf16(cs.scale), dev_bf16(cs.offset), bits)
+    y_plain = any4.any4_gemm(dev_bf16(cs.x), codes_dev, *args)
+    y_re = any4.any4_gemm_repacked(dev_bf16(cs.x), rcodes, *args)
+    torch.cuda.synchronize()
+    assert torch.equal(y_plain.view(torch.int16), y_re.view(torch.int16))
+    check_gemm(y_re, y64, oracle.rms(y64), ("repacked", M, N, K, bits))
+
+
+def test_gemm_repacked_needs_a_table(any4):
+    cs = inputs.make_case(1, 16, 128, 4, 3)
+    rcodes = any4.any4_repack(any4.any4_pack(torch.from_numpy(cs.codes_u8).cuda(), 4), 4)
+    with pytest.raises(any4.Any4Error):
+        any4.any4_gemm_repacked(dev_bf16(cs.x), rcodes, None, dev_bf16(cs.scale), dev_bf16(cs.offset), 4)
+
+
 # ------------------------------------------------------------------------------ full benchmark shapes, sampled rows
 SAMPLE_ROWS = 48
 
@@ -237,6 +276,7 @@ def sampled_rows_check(any4, oracle, shape_name, N, K, bits, Ms, seed):
     Mmax = max(Ms)
     cs = inputs.make_case(Mmax, N, K, bits, seed)
     codes_dev = any4.any4_pack(torch.from_numpy(cs.codes_u8).cuda(), bits)
+    rcodes = any4.any4_repack(codes_dev, bits)
     lut, scale, offset = dev_bf16(cs.lut), dev_bf16(cs.scale), dev_bf16(cs.offset)
     rng = np.random.default_rng(seed + 1)
     rows = np.unique(np.concatenate([[0, 1, N - 2, N - 1], rng.integers(0, N, SAMPLE_ROWS)]))
@@ -253,7 +293,9 @@ def sampled_rows_check(any4, oracle, shape_name, N, K, bits, Ms, seed):
         x = cs.x[:M]
         y64 = oracle.gemm(x, packed_rows, cs.lut[rows], cs.scale[rows], cs.offset[rows], K, bits, threads=8)
         y = any4.any4_gemm(dev_bf16(x), codes_dev, lut, scale, offset, bits)
+        y_re = any4.any4_gemm_repacked(dev_bf16(x), rcodes, lut, scale, offset, bits)
         torch.cuda.synchronize()
+        assert torch.equal(y.view(torch.int16), y_re.view(torch.int16)), (shape_name, M, "re-laid-out codes")
         worst = max(worst, check_gemm(y[:, idx], y64, oracle.rms(y64), (shape_name, M, N, K, bits)))
     return worst
 
