@@ -166,20 +166,26 @@ def main():
 
     # ------------------------------------------------------------------ context measurements
     def time_gemm(g, reps, rotate=None, fn=None):
-        """median microseconds of one launch (event pair per launch); rotate = list of
-        equivalent problems to cycle through so weights come from HBM."""
+        """microseconds of one launch: `reps` launches, cycling through `rotate` (equivalent problems,
+        so that weights come from HBM), captured in one HIP graph and replayed; events around the replay.
+        (Eager launches with an event pair each add several microseconds to kernels this short.)"""
         probs = rotate or [g]
         fn = fn or launch
         for p in probs[:2]:
             fn(p)
         torch.cuda.synchronize()
-        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
-        for r in range(reps):
-            ev[r][0].record()
-            fn(probs[r % len(probs)])
-            ev[r][1].record()
+        gr = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gr):
+            for r in range(reps):
+                fn(probs[r % len(probs)])
+        gr.replay()
         torch.cuda.synchronize()
-        return float(np.median([a.elapsed_time(b) * 1e3 for a, b in ev]))
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        gr.replay()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) * 1e3 / reps
 
     if args.extras:
         del graph

@@ -425,29 +425,39 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
     //      codes of the ring and the small inputs.
     // activations of the wavefront's groups as A operands: lane (m = n, q), MFMA j of group gi holds
     // x[m][(gw0 + gi) * 128 + q * 32 + j * 8 .. + 8]; rows m >= M and missing groups are zero.
-    // Up to kStageRows rows: the wavefront fetches each row's GW * 128 activations with ONE 16-byte
-    // load per lane and re-distributes them through LDS (the partial-sum buffer is idle until the
-    // first tile), instead of 4 * GW loads in which most lanes fetch what they will zero anyway.
-    constexpr int kStageRows = 2;
-    static_assert(kStageRows * GW * 256 * kWaves <= kRedBytes, "activation staging lives in the partial-sum buffer");
-    const bool compact = M <= kStageRows;                 // the same for every thread
+    // The wavefront fetches each row's GW * 128 activations with ONE 16-byte load per lane (a
+    // contiguous kilobyte per instruction) and re-distributes them to the operand layout through
+    // LDS, instead of 4 * GW loads per lane that each pick 16-byte pieces out of 16 rows.  One or
+    // two rows go through the partial-sum buffer (idle until the first tile; every wavefront has a
+    // slice of its own, no barrier).  More rows are fetched 8 or 16 at a time (rows past M repeat
+    // row M - 1 so that the loads are unconditional) and go, kStageRows at a pass, through the table
+    // buffers, which are idle until the first table is built - after a barrier in that case.
+    constexpr int kStageRows = BITS == 4 ? 8 : (BITS == 2 ? 16 : 4);
+    static_assert(2 * GW * 256 * kWaves <= kRedBytes, "one or two rows are staged in the partial-sum buffer");
+    static_assert(kStageRows * GW * 256 * kWaves <= table_bytes(BITS) + kRedBytes, "more rows are staged in the table buffers");
+    const bool compact = M <= 2;                          // the same for every thread
+    const bool has = lane * 8 < ngw * kGroup;             // GW * 128 = up to 64 lanes x 8 elements
     uint4 xa[GW][4];
-    uint4 xraw[kStageRows];
+    uint4 xraw[kTile];
     if (compact) {
-        const bool has = lane * 8 < ngw * kGroup;        // GW * 128 = up to 64 lanes x 8 elements
 #pragma unroll
-        for (int m = 0; m < kStageRows; ++m) {
+        for (int m = 0; m < 2; ++m) {
             xraw[m] = make_uint4(0, 0, 0, 0);
             if (m < M && has)
                 xraw[m] = *reinterpret_cast<const uint4*>(p.x + (int64_t)m * K + (int64_t)gw0 * kGroup + lane * 8);
         }
     } else {
-        const uint16_t* xrow = p.x + (int64_t)min(n, M - 1) * K + q * 32;
+        const uint16_t* xsrc = p.x + (int64_t)gw0 * kGroup + (has ? lane : 0) * 8;
+        auto fetch_rows = [&](auto nr_) {
+            constexpr int NR = decltype(nr_)::value;
 #pragma unroll
-        for (int gi = 0; gi < GW; ++gi)
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                xa[gi][j] = *reinterpret_cast<const uint4*>(xrow + (int64_t)group_of(gi) * kGroup + j * 8);
+            for (int m = 0; m < NR; ++m) {
+                const uint4 v = *reinterpret_cast<const uint4*>(xsrc + (int64_t)min(m, M - 1) * K);
+                xraw[m] = has ? v : make_uint4(0, 0, 0, 0);
+            }
+        };
+        if (M <= 8) fetch_rows(std::integral_constant<int, 8>{});
+        else fetch_rows(std::integral_constant<int, kTile>{});
     }
     LutSrc lut0;
     if constexpr (AUX) {
@@ -470,31 +480,36 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
         }
     }
     ANY4_STOP(4);
-    if (compact) {
-        // row m of this wavefront at stage + m * (GW * 16) uint4; a lane's MFMA-j piece of group gi
-        // is uint4 number gi * 16 + q * 4 + j of its row
-        uint4* stage = reinterpret_cast<uint4*>(red) + w * (kStageRows * GW * 16);
 #pragma unroll
-        for (int m = 0; m < kStageRows; ++m)
-            if (m < M && lane < GW * 16) stage[m * (GW * 16) + lane] = xraw[m];
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");          // same wavefront wrote it: no barrier needed
+    for (int gi = 0; gi < GW; ++gi)
 #pragma unroll
-        for (int gi = 0; gi < GW; ++gi)
+        for (int j = 0; j < 4; ++j) xa[gi][j] = make_uint4(0, 0, 0, 0);
+    {
+        // row m of a pass at stage + m * (GW * 16) uint4 of the wavefront's slice; a lane's MFMA-j piece
+        // of group gi is uint4 number gi * 16 + q * 4 + j of its row.  Lanes of groups the wavefront
+        // does not have hold zeros.  The slice is written and read by this wavefront only.
+        auto stage_pass = [&](uint4* stage, int r0, auto rows_) {
+            constexpr int ROWS = decltype(rows_)::value;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) xa[gi][j] = make_uint4(0, 0, 0, 0);
-        if (n < M) {
+            for (int m = 0; m < ROWS; ++m)
+                if (lane < GW * 16 && r0 + m < M) stage[m * (GW * 16) + lane] = xraw[r0 + m];
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            if (n >= r0 && n < min(M, r0 + ROWS)) {
 #pragma unroll
-            for (int gi = 0; gi < GW; ++gi)
+                for (int gi = 0; gi < GW; ++gi)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) xa[gi][j] = stage[n * (GW * 16) + gi * 16 + q * 4 + j];
+                    for (int j = 0; j < 4; ++j) xa[gi][j] = stage[(n - r0) * (GW * 16) + gi * 16 + q * 4 + j];
+            }
+        };
+        if (compact) {
+            stage_pass(reinterpret_cast<uint4*>(red) + w * (2 * GW * 16), 0, std::integral_constant<int, 2>{});
+        } else {
+            uint4* stage = reinterpret_cast<uint4*>(smem) + w * (kStageRows * GW * 16);
+#pragma unroll
+            for (int r0 = 0; r0 < kTile; r0 += kStageRows)
+                if (r0 < M) stage_pass(stage, r0, std::integral_constant<int, kStageRows>{});
+            lds_barrier();                                 // before anybody builds a table over a slice
         }
-    } else {
-        const bool live_row = n < M;
-#pragma unroll
-        for (int gi = 0; gi < GW; ++gi)
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                if (!(live_row && gi < ngw)) xa[gi][j] = make_uint4(0, 0, 0, 0);
     }
 
     // group sums of the activations -> A operand of the offset MFMA (q == 0 lanes: hi parts in
