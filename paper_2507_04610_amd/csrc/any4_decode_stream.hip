@@ -758,48 +758,53 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
             }
             lds_barrier();
             ANY4_STOP(12);
-            // All outputs of all listed tiles.  A thread takes kCombine outputs at a time and issues the
-            // loads of four slabs of all of them before it adds anything (one wait per 4 * kCombine
-            // loads: the partial sums come from other compute units, a load costs a trip to memory);
+            // All outputs of all listed tiles.  A thread takes UC outputs at a time and issues the
+            // loads of KC slabs of all of them before it adds anything (one wait per KC * UC loads:
+            // the partial sums come from other compute units, a load costs a trip to memory);
             // outputs past the end repeat the last one and slabs past the end repeat the last slab, so
             // that every load is unconditional, and are left out of the sum / not stored.  The sum runs
             // over the slabs in slab order whatever the batching.
-            constexpr int kCombine = 4;
             const int nlast = lastlist[0];
             const int nout = nlast * M * kTile;
             const int64_t slab_stride = (int64_t)M * N;
-            for (int base = 0; base < nout; base += kThreads * kCombine) {
-                const float* src[kCombine];
-                int64_t dst[kCombine];
-                bool live[kCombine];
-                float s[kCombine];
+            auto combine = [&](auto kc_, auto uc_) {
+                constexpr int KC = decltype(kc_)::value, UC = decltype(uc_)::value;
+                for (int base = 0; base < nout; base += kThreads * UC) {
+                    const float* src[UC];
+                    int64_t dst[UC];
+                    bool live[UC];
+                    float s[UC];
 #pragma unroll
-                for (int u = 0; u < kCombine; ++u) {
-                    const int raw = base + u * kThreads + tid, idx = min(raw, nout - 1);
-                    const int e = idx / (M * kTile), o = idx - e * (M * kTile);
-                    const int m = o >> 4, nn = o & 15;
-                    const int64_t col = (int64_t)lastlist[1 + e] * kTile + nn;
-                    live[u] = raw < nout && col < N;
-                    dst[u] = (int64_t)m * N + min(col, N - 1);
-                    src[u] = p.partial + dst[u];
-                    s[u] = 0.f;
+                    for (int u = 0; u < UC; ++u) {
+                        const int raw = base + u * kThreads + tid, idx = min(raw, nout - 1);
+                        const int e = idx / (M * kTile), o = idx - e * (M * kTile);
+                        const int m = o >> 4, nn = o & 15;
+                        const int64_t col = (int64_t)lastlist[1 + e] * kTile + nn;
+                        live[u] = raw < nout && col < N;
+                        dst[u] = (int64_t)m * N + min(col, N - 1);
+                        src[u] = p.partial + dst[u];
+                        s[u] = 0.f;
+                    }
+                    for (int k0 = 0; k0 < p.slabs; k0 += KC) {
+                        float v[KC][UC];
+#pragma unroll
+                        for (int kk = 0; kk < KC; ++kk)
+#pragma unroll
+                            for (int u = 0; u < UC; ++u)
+                                v[kk][u] = splitk_load(src[u] + (int64_t)min(k0 + kk, p.slabs - 1) * slab_stride);
+#pragma unroll
+                        for (int kk = 0; kk < KC; ++kk)
+#pragma unroll
+                            for (int u = 0; u < UC; ++u) s[u] += k0 + kk < p.slabs ? v[kk][u] : 0.f;
+                    }
+#pragma unroll
+                    for (int u = 0; u < UC; ++u)
+                        if (live[u]) p.y[dst[u]] = (uint16_t)f32_to_bf16(s[u]);
                 }
-                for (int k0 = 0; k0 < p.slabs; k0 += 4) {
-                    float v[4][kCombine];
-#pragma unroll
-                    for (int kk = 0; kk < 4; ++kk)
-#pragma unroll
-                        for (int u = 0; u < kCombine; ++u)
-                            v[kk][u] = splitk_load(src[u] + (int64_t)min(k0 + kk, p.slabs - 1) * slab_stride);
-#pragma unroll
-                    for (int kk = 0; kk < 4; ++kk)
-#pragma unroll
-                        for (int u = 0; u < kCombine; ++u) s[u] += k0 + kk < p.slabs ? v[kk][u] : 0.f;
-                }
-#pragma unroll
-                for (int u = 0; u < kCombine; ++u)
-                    if (live[u]) p.y[dst[u]] = (uint16_t)f32_to_bf16(s[u]);
-            }
+            };
+            // few slabs: more outputs at a time instead (no repeated loads of the last slab)
+            if (p.slabs <= 2) combine(std::integral_constant<int, 2>{}, std::integral_constant<int, 8>{});
+            else combine(std::integral_constant<int, 4>{}, std::integral_constant<int, 4>{});
             lds_barrier();
             if (tid == 0) lastlist[0] = 0;
             lds_barrier();
