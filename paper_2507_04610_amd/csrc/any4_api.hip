@@ -16,6 +16,7 @@ static int shape_check(int64_t N, int64_t K, int bits) {
 
 constexpr int kDecodeMaxM = 16;
 constexpr int kStreamMaxM = 16;
+constexpr int kChunkedMaxM = 128;      // above this the matrix-core kernel is always taken
 
 // Compute units of the current device (256 on MI355X); only shapes the work split, never results.
 int device_compute_units() {
@@ -38,6 +39,33 @@ GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int bits) {
             p.ksplit = p.sp.slabs;
             p.workspace = p.sp.workspace;
             return p;
+        }
+    }
+    if (M > kStreamMaxM && M <= kChunkedMaxM && N <= ((int64_t)1 << 35)) {
+        // A few dozen rows of x fill a fraction of one 256-row tile of the matrix-core kernel, whose
+        // time does not depend on M below 256; streaming the weights once per 16 rows is faster while
+        //   launches * (6.5 us + bytes of codes / 3.8 TB/s)  <  rounds * (8 us + step * K / 64),
+        // step = 0.95 us with few blocks in flight up to 1.3 us with every compute unit busy
+        // (measured constants of the two kernels; a block is 256 x 128 outputs).
+        const int cus = device_compute_units();
+        const double launches = (double)((M + kStreamMaxM - 1) / kStreamMaxM);
+        const double t_stream = launches * (6.5 + (double)N * (double)K * bits / 8.0 / 3.8e6);
+        const int64_t blocks = (N + 127) / 128;
+        const double rounds = (double)((blocks + cus - 1) / cus);
+        const double busy = blocks >= cus ? 1.0 : (double)blocks / cus;
+        const double t_matrix = rounds * (8.0 + (0.95 + 0.35 * busy) * (double)(K / 64));
+        if (t_stream < t_matrix) {
+            const int tail_rows = (int)(M % kStreamMaxM);
+            const StreamPlan full = plan_stream(kStreamMaxM, N, K, cus);
+            const StreamPlan tail = tail_rows ? plan_stream(tail_rows, N, K, cus) : full;
+            if (full.gw > 0 && tail.gw > 0) {
+                p.decode = p.stream = p.chunked = true;
+                p.sp = full;
+                p.sp_tail = tail;
+                p.ksplit = full.slabs;
+                p.workspace = full.workspace > tail.workspace ? full.workspace : tail.workspace;
+                return p;
+            }
         }
     }
     p.decode = M <= kDecodeMaxM;
@@ -127,7 +155,15 @@ static int gemm_any_layout(const uint16_t* x, const uint32_t* codes, bool repack
     if (plan.workspace > 0 && (!workspace || workspace_bytes < plan.workspace)) return ANY4_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t e;
-    if (plan.stream) {
+    if (plan.chunked) {
+        // launches run one after the other on the stream and leave the workspace's counters clean
+        e = hipSuccess;
+        for (int64_t m0 = 0; m0 < M && e == hipSuccess; m0 += kStreamMaxM) {
+            const int64_t rows = M - m0 < kStreamMaxM ? M - m0 : kStreamMaxM;
+            e = launch_decode_stream(x + m0 * K, codes, lut, scale, offset, rows, N, K, bits, repacked,
+                                     rows == kStreamMaxM ? plan.sp : plan.sp_tail, y + m0 * N, workspace, s);
+        }
+    } else if (plan.stream) {
         e = launch_decode_stream(x, codes, lut, scale, offset, M, N, K, bits, repacked, plan.sp, y, workspace, s);
     } else if (plan.decode) {
         e = launch_decode(x, codes, lut, scale, offset, M, N, K, bits, plan, y, static_cast<float*>(workspace), s);

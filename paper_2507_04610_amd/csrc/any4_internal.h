@@ -25,6 +25,8 @@ struct GemmPlan {
     bool decode;          // true: memory-bound small-M kernel, false: matrix-core kernel
     bool stream;          // decode only: persistent streaming kernel; false: one wavefront per (row, K slice)
     StreamPlan sp;
+    bool chunked;         // M just above the small-M range: the streaming kernel, 16 rows of x per launch
+    StreamPlan sp_tail;   // chunked only: the plan of the last launch when M is not a multiple of 16
     int ksplit;           // number of K slices whose fp32 partials are reduced in a 2nd pass
     size_t workspace;     // bytes of scratch: K-slice partials (decode) or group sums of x (matrix-core path)
 };

@@ -229,6 +229,16 @@ def test_gemm_rejects_small_workspace_and_leaves_output_alone(any4):
     assert torch.all(y == 7.0)
 
 
+@pytest.mark.parametrize("bits", (4, 3, 2))
+@pytest.mark.parametrize("M,N,K", [(17, 64, 4096), (32, 256, 4096), (37, 100, 14336), (64, 512, 2048),
+                                   (128, 96, 8192)])
+def test_gemm_few_dozen_rows(any4, oracle, bits, M, N, K):
+    """M just above 16: served by the streaming kernel, 16 rows of x per launch (ragged last launch,
+    K slabs that share one workspace from launch to launch), or by the matrix-core kernel - whichever
+    the library picks, the result must be the same GEMM."""
+    run_gemm_case(any4, oracle, M, N, K, bits, seed=inputs.case_seed(6, bits, M))
+
+
 # ------------------------------------------------------------------------------ tile-major re-layout
 @pytest.mark.parametrize("bits", (4, 3, 2))
 @pytest.mark.parametrize("N,K", [(16, 128), (21, 256), (1, 128), (257, 1152), (64, 4096), (5, 14336)])
