@@ -82,8 +82,10 @@ int any4_dequant(const uint32_t* codes, const uint16_t* lut, const uint16_t* sca
  * materialised (section 4.2: weights are dequantised on the fly inside the GEMM).
  * Products are accumulated in fp32 (order unspecified but fixed for given shapes: the
  * result is reproducible run to run); y is rounded to bf16, round-to-nearest-even.
- * Small M (<= 16, token generation) takes a memory-bound kernel, larger M a
- * matrix-core kernel; the choice depends only on (M, N, K, bits).
+ * Small M (<= 16, token generation) takes a memory-bound kernel, large M a
+ * matrix-core kernel, M up to 128 whichever of the two a cost model expects to be
+ * faster (the memory-bound kernel then runs once per 16 rows of x); the choice depends
+ * only on (M, N, K, bits) and the number of compute units of the device.
  *   x          in   bf16 [M][K]
  *   lut        as for any4_dequant, including NULL = int4 grid for bits = 4
  *   y          out  bf16 [M][N], fully overwritten
