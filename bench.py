@@ -55,7 +55,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only (--gpus 1); the path shards without "
-              "communication along N and with one small all-reduce along K, see DESIGN.md",
+              "communication along N and with one small all-reduce along K.",
               file=sys.stderr)
         sys.exit(2)
 
