@@ -44,16 +44,23 @@ GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int bits) {
     if (M > kStreamMaxM && M <= kChunkedMaxM && N <= ((int64_t)1 << 35)) {
         // A few dozen rows of x fill a fraction of one 256-row tile of the matrix-core kernel, whose
         // time does not depend on M below 256; streaming the weights once per 16 rows is faster while
-        //   launches * (6.5 us + bytes of codes / 3.8 TB/s)  <  rounds * (8 us + step * K / 64),
-        // step = 0.95 us with few blocks in flight up to 1.3 us with every compute unit busy
-        // (measured constants of the two kernels; a block is 256 x 128 outputs).
+        //   launches * (6.5 us + bytes of codes / 3.8 TB/s)
+        // stays below the matrix-core kernel's time: per round of blocks 8 us + step * K / 64 with
+        // step = 0.95 us (few blocks in flight) .. 1.3 us (every compute unit busy), the last round
+        // divided by its number of K slices plus 3 + 2 * slices us for adding them up (all constants
+        // measured on the two kernels).
         const int cus = device_compute_units();
         const double launches = (double)((M + kStreamMaxM - 1) / kStreamMaxM);
         const double t_stream = launches * (6.5 + (double)N * (double)K * bits / 8.0 / 3.8e6);
-        const int64_t blocks = (N + 127) / 128;
-        const double rounds = (double)((blocks + cus - 1) / cus);
-        const double busy = blocks >= cus ? 1.0 : (double)blocks / cus;
-        const double t_matrix = rounds * (8.0 + (0.95 + 0.35 * busy) * (double)(K / 64));
+        const PrefillPlan pp = plan_prefill(M, N, K, cus);
+        const double ksteps = (double)(K / 64);
+        const int64_t last = pp.tiles % cus;
+        double t_matrix = (double)(pp.tiles / cus) * (8.0 + 1.3 * ksteps);
+        if (last > 0) {
+            const double busy = (double)(last * pp.tail_s) / cus;
+            t_matrix += 8.0 + (0.95 + 0.35 * (busy < 1.0 ? busy : 1.0)) * ksteps / pp.tail_s +
+                        (pp.tail_s > 1 ? 3.0 + 2.0 * pp.tail_s : 0.0);
+        }
         if (t_stream < t_matrix) {
             const int tail_rows = (int)(M % kStreamMaxM);
             const StreamPlan full = plan_stream(kStreamMaxM, N, K, cus);
@@ -82,7 +89,7 @@ GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int bits) {
         p.ksplit = (int)want;
     }
     if (p.decode) p.workspace = p.ksplit > 1 ? (size_t)p.ksplit * (size_t)M * (size_t)N * sizeof(float) : 0;
-    else p.workspace = prefill_workspace_bytes(M, K);
+    else p.workspace = prefill_workspace_bytes(M, N, K, device_compute_units());
     return p;
 }
 
@@ -168,7 +175,7 @@ static int gemm_any_layout(const uint16_t* x, const uint32_t* codes, bool repack
     } else if (plan.decode) {
         e = launch_decode(x, codes, lut, scale, offset, M, N, K, bits, plan, y, static_cast<float*>(workspace), s);
     } else {
-        e = launch_prefill(x, codes, lut, scale, offset, M, N, K, bits, repacked, y, workspace, s);
+        e = launch_prefill(x, codes, lut, scale, offset, M, N, K, bits, repacked, device_compute_units(), y, workspace, s);
     }
     return e == hipSuccess ? ANY4_OK : ANY4_ERR_HIP;
 }

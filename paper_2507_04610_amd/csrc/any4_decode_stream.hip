@@ -134,34 +134,6 @@ __device__ __forceinline__ float sum8(const uint4& v) {
            ((bf16lo_to_f32(v.z) + bf16hi_to_f32(v.z)) + (bf16lo_to_f32(v.w) + bf16hi_to_f32(v.w)));
 }
 
-// One arrival at a tile's counter by a single thread; true if this was the last of `ksplit`.
-// The caller has made its partial sums visible (stores issued and waited for) beforehand.
-// A counter word is (tag << 8 | arrivals).  The last arrival of a tile puts its counter back to
-// "tag, 0", so a workspace that has served a call is clean for the next one and an arrival is ONE
-// atomic add; a word without the tag (a workspace used for the first time, or memory that held
-// something else) is claimed with a compare-and-swap instead.
-constexpr unsigned long long kArriveTag = 0x00A4C0DE5EED17ull;          // 56 bits
-__device__ __forceinline__ bool arrive_one(unsigned long long* c, int ksplit) {
-    unsigned long long old = __hip_atomic_fetch_add(c, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    unsigned long long cnt;
-    if ((old >> 8) == kArriveTag) {
-        cnt = (old & 0xFFull) + 1ull;
-    } else {
-        // the add above went into a foreign word and is dropped with it
-        old += 1ull;
-        for (;;) {
-            cnt = ((old >> 8) == kArriveTag) ? (old & 0xFFull) + 1ull : 1ull;
-            const unsigned long long nv = (kArriveTag << 8) | cnt;
-            if (__hip_atomic_compare_exchange_strong(c, &old, nv, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
-                                                     __HIP_MEMORY_SCOPE_AGENT))
-                break;
-        }
-    }
-    const bool last = cnt == (unsigned long long)ksplit;
-    if (last) __hip_atomic_store(c, kArriveTag << 8, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    return last;
-}
-
 // BITS    code width: 4, 3 or 2
 // GW      groups (of 128 weights) a wavefront owns: 1, 2 or 4
 // AUX     tables, scales and offsets of a tile are loaded by one wavefront and shared through LDS;

@@ -48,7 +48,7 @@ hipError_t launch_decode_stream(const uint16_t* x, const uint32_t* codes, const 
 hipError_t launch_reduce_slices(const float* partial, int ksplit, int64_t MN, uint16_t* y, hipStream_t stream);
 hipError_t launch_prefill(const uint16_t* x, const uint32_t* codes, const uint16_t* lut,
                           const uint16_t* scale, const uint16_t* offset,
-                          int64_t M, int64_t N, int64_t K, int bits, bool repacked,
+                          int64_t M, int64_t N, int64_t K, int bits, bool repacked, int cus,
                           uint16_t* y, void* workspace, hipStream_t stream);
 // Tile-major re-layout of the packed codes (any4_repack).
 hipError_t launch_repack(const uint32_t* codes, int64_t N, int64_t K, int bits, uint32_t* out, hipStream_t stream);
@@ -56,7 +56,14 @@ hipError_t launch_repack(const uint32_t* codes, int64_t N, int64_t K, int bits, 
 // Matrix-core path: padded length of the "group" dimension (two bf16 columns per group of 128,
 // rounded up to the MFMA K granularity of 16) and the scratch it needs for the group sums of x.
 inline int prefill_kp(int64_t K) { return (int)((2 * (K / 128) + 15) / 16 * 16); }
-size_t prefill_workspace_bytes(int64_t M, int64_t K);
+// its work split (tiles of 256 x 128 outputs; the tiles of a thin last round are cut along K) and scratch
+struct PrefillPlan {
+    int64_t gm, tiles, tail_tiles;
+    int tail_s;
+    size_t xsums_bytes, counter_bytes, partial_bytes;
+};
+PrefillPlan plan_prefill(int64_t M, int64_t N, int64_t K, int cus);
+size_t prefill_workspace_bytes(int64_t M, int64_t N, int64_t K, int cus);
 
 // Read-only streaming kernel for the benchmark's "what does a launch that reads these bytes cost" figure.
 hipError_t launch_stream_read(const void* p, size_t bytes, uint32_t magic, uint32_t* sink, hipStream_t stream);

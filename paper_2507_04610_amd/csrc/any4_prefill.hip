@@ -27,6 +27,7 @@
 // the barrier keeps in step, then leave the matrix cores idle while both stage.
 #include "any4_device.h"
 #include "any4_internal.h"
+#include "any4_splitk.h"
 #include <type_traits>
 
 namespace any4 {
@@ -85,16 +86,30 @@ __global__ __launch_bounds__(PTHREADS, 1) void prefill_kernel(
     const uint16_t* __restrict__ x, const uint32_t* __restrict__ codes,
     const uint16_t* __restrict__ lut, const uint16_t* __restrict__ scale,
     const uint16_t* __restrict__ offset, const uint16_t* __restrict__ xsums, int KP,
-    int64_t M, int64_t N, int64_t K, int repacked, uint16_t* __restrict__ y) {
+    int64_t M, int64_t N, int64_t K, int repacked, int gm, int tail_first, int tail_s,
+    unsigned long long* __restrict__ counters, float* __restrict__ partial, uint16_t* __restrict__ y) {
     constexpr int L = 1 << BITS;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     uint32_t* table = reinterpret_cast<uint32_t*>(smem + kTableOff);      // [PBN / 8][L][32]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
-    const int64_t m0 = (int64_t)blockIdx.x * PBM, n0 = (int64_t)blockIdx.y * PBN;
     const int64_t G = K / kGroup, RW = row_words(K, BITS);
-    const int T = (int)(2 * G);                                           // K steps
+    // Blocks below tail_first own a whole output tile.  The tiles of the last, partly filled round
+    // of blocks are cut along K into tail_s slices of whole groups, one block each, so that the
+    // round keeps every compute unit busy for 1 / tail_s of a tile's time; the slices' fp32 results
+    // meet in the workspace and the block that arrives last adds them in slice order.
+    int tile = blockIdx.x, slice = -1;
+    int g_lo = 0, g_hi = (int)G;
+    if (tile >= tail_first) {
+        const int idx = tile - tail_first;
+        tile = tail_first + idx / tail_s;
+        slice = idx % tail_s;
+        g_lo = (int)(slice * G / tail_s);
+        g_hi = (int)((slice + 1) * G / tail_s);
+    }
+    const int64_t m0 = (int64_t)(tile % gm) * PBM, n0 = (int64_t)(tile / gm) * PBN;   // m fastest: an XCD keeps its rows of x
+    const int S0 = 2 * g_lo, T = 2 * g_hi;                                // this block's K steps
 
     // ---- staging roles.  Weights: thread -> (row, 16-code quarter of the K step); rows past N are
     //      clamped (computed, never stored).  Activations: thread -> 4 rows, one 16-byte piece each.
@@ -261,9 +276,9 @@ __global__ __launch_bounds__(PTHREADS, 1) void prefill_kernel(
     using No = std::false_type;
 
     uint32_t q0[2], q1[2];
-    fetch_x(0);                                                // in flight while the tables are filled
-    fetch_q(q0, 0);
-    fetch_q(q1, 1);
+    fetch_x(S0);                                               // in flight while the tables are filled
+    fetch_q(q0, S0);
+    fetch_q(q1, S0 + 1);
     // per-row tables of this block's weight rows (rows past N are clamped: they are never stored):
     // one thread fetches 8 bytes (4 entries) of a row and writes each entry's 4 adjacent copies at once
     {
@@ -300,8 +315,8 @@ __global__ __launch_bounds__(PTHREADS, 1) void prefill_kernel(
             *reinterpret_cast<lds_u4>(wwr + c * 16) =
                 u32x4{v[0] | (v[1] << 16), v[2] | (v[3] << 16), v[4] | (v[5] << 16), v[6] | (v[7] << 16)};
         }
-        fetch_q(q0, min(2, T - 1));
-        fetch_x(1);
+        fetch_q(q0, min(S0 + 2, T - 1));
+        fetch_x(S0 + 1);
     }
     lds_barrier();
 
@@ -310,9 +325,9 @@ __global__ __launch_bounds__(PTHREADS, 1) void prefill_kernel(
     //      writes freed the registers), codes from set (s + 1) % 2, which it then refills with the
     //      codes of step s + 3.  The last step stages a repeat of step T - 1 into a buffer that is
     //      not read again.
-    for (int64_t g = 0; g < G; ++g) {
+    for (int g = g_lo; g < g_hi; ++g) {
         const uint32_t sraw0 = scol[0][g], sraw1 = scol[1][g];
-        const int s = (int)(2 * g);
+        const int s = 2 * g;
         step(B0{}, Yes{}, No{}, q1, min(s + 3, T - 1), min(s + 2, T - 1), 0u, 0u);
         lds_barrier();
         step(B1{}, No{}, Yes{}, q0, min(s + 4, T - 1), min(s + 3, T - 1), sraw0, sraw1);
@@ -321,7 +336,7 @@ __global__ __launch_bounds__(PTHREADS, 1) void prefill_kernel(
 
     // ---- offset term: a few more K steps over the group dimension (activation group sums split into
     //      bf16 hi + lo in columns 2g, 2g+1; both columns meet offset[n][g]); unscaled
-    for (int64_t k0 = 0; k0 < KP; k0 += PBK) {
+    for (int k0 = 2 * g_lo / PBK * PBK; k0 < 2 * g_hi; k0 += PBK) {
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
             const uint16_t* src = xsums + min(m0 + p * 64 + xr_row, M - 1) * KP + xc8 * 8 + k0;
@@ -330,8 +345,8 @@ __global__ __launch_bounds__(PTHREADS, 1) void prefill_kernel(
         uint32_t pk[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            const int64_t gg = (k0 + wq * 16 + 2 * j) >> 1;
-            const uint32_t b = gg < G ? offset[wn_glob * G + gg] : 0u;
+            const int gg = (k0 + wq * 16 + 2 * j) >> 1;
+            const uint32_t b = gg >= g_lo && gg < g_hi ? offset[wn_glob * G + gg] : 0u;
             pk[j] = b | (b << 16);
         }
 #pragma unroll
@@ -343,17 +358,69 @@ __global__ __launch_bounds__(PTHREADS, 1) void prefill_kernel(
         lds_barrier();
     }
 
-    // ---- store: accumulator element v of a lane is row 8*(v/4) + 4*(lane/32) + v%4, column lane%32
+    // ---- store (accumulator element v of a lane is row 8*(v/4) + 4*(lane/32) + v%4, column lane%32 of its
+    //      32 x 32 tile)
+    auto store_tile = [&](int i, int j, const f32x16& r) {
+        const int64_t n = n0 + wn * 64 + j * 32 + (lane & 31);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int64_t m = m0 + wm * 64 + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+            if (m < M && n < N) y[m * N + n] = (uint16_t)f32_to_bf16(r[v]);
+        }
+    };
+    if (slice < 0) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) store_tile(i, j, acc[i][j]);
+        return;
+    }
+    // ---- a K slice: its fp32 sums go to the workspace; the last slice of the tile to arrive adds them all
+    float* mine = partial + ((int64_t)(tile - tail_first) * tail_s + slice) * (PBM * PBN);
+    auto elem = [&](int i, int j, int v) -> int {
+        return (wm * 64 + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3)) * PBN + wn * 64 + j * 32 + (lane & 31);
+    };
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                // through an opaque copy: with the accumulator vector itself as the source of the atomic
+                // stores the compiler copies all 64 accumulators inside the main loop on every iteration
+                float t = acc[i][j][v];
+                asm volatile("" : "+v"(t));
+                splitk_store(mine + elem(i, j, v), t);
+            }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");           // this thread's sums are out
+    lds_barrier();                                             // ... and so are the whole block's
+    int* flag = reinterpret_cast<int*>(smem);
+    if (tid == 0) *flag = arrive_one(counters + (tile - tail_first), tail_s) ? 1 : 0;
+    lds_barrier();
+    if (*flag == 0) return;
+    const float* all = partial + (int64_t)(tile - tail_first) * tail_s * (PBM * PBN);
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
-            const int64_t n = n0 + wn * 64 + j * 32 + (lane & 31);
+            f32x16 sum;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int64_t m = m0 + wm * 64 + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
-                if (m < M && n < N) y[m * N + n] = (uint16_t)f32_to_bf16(acc[i][j][v]);
+            for (int v = 0; v < 16; ++v) sum[v] = 0.f;
+            for (int sl = 0; sl < tail_s; sl += 2) {           // two slices' worth of loads in flight
+                float a[16], b[16];
+                const int sl1 = min(sl + 1, tail_s - 1);
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    a[v] = splitk_load(all + (int64_t)sl * (PBM * PBN) + elem(i, j, v));
+                    b[v] = splitk_load(all + (int64_t)sl1 * (PBM * PBN) + elem(i, j, v));
+                }
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    sum[v] += a[v];
+                    if (sl + 1 < tail_s) sum[v] += b[v];
+                }
             }
+            store_tile(i, j, sum);
         }
 }
 
@@ -361,31 +428,58 @@ constexpr size_t prefill_lds_bytes(int bits) {
     return (size_t)kTableOff + (size_t)PBN * (1 << bits) * 4 * 4;
 }
 
-size_t prefill_workspace_bytes(int64_t M, int64_t K) {
-    return (size_t)M * (size_t)prefill_kp(K) * sizeof(uint16_t);
+// Work split: whole tiles, and K slices for the tiles of a last round that would leave more than
+// half of the compute units idle (also the only round of a small problem).
+PrefillPlan plan_prefill(int64_t M, int64_t N, int64_t K, int cus) {
+    PrefillPlan p{};
+    const int64_t gm = (M + PBM - 1) / PBM, gn = (N + PBN - 1) / PBN, G = K / kGroup;
+    p.gm = gm;
+    p.tiles = gm * gn;
+    p.tail_tiles = 0;
+    p.tail_s = 1;
+    const int64_t r = p.tiles % cus;
+    if (r > 0) {
+        int64_t sl = cus / r;
+        if (sl > 8) sl = 8;
+        if (sl > G / 4) sl = G / 4;                            // at least four groups (eight K steps) per slice
+        if (sl >= 2) { p.tail_tiles = r; p.tail_s = (int)sl; }
+    }
+    p.xsums_bytes = ((size_t)M * (size_t)prefill_kp(K) * sizeof(uint16_t) + 255) / 256 * 256;
+    p.counter_bytes = p.tail_tiles ? splitk_counter_bytes(p.tail_tiles) : 0;
+    p.partial_bytes = (size_t)p.tail_tiles * (size_t)p.tail_s * (PBM * PBN) * sizeof(float);
+    return p;
+}
+
+size_t prefill_workspace_bytes(int64_t M, int64_t N, int64_t K, int cus) {
+    const PrefillPlan p = plan_prefill(M, N, K, cus);
+    return p.xsums_bytes + p.counter_bytes + p.partial_bytes;
 }
 
 hipError_t launch_prefill(const uint16_t* x, const uint32_t* codes, const uint16_t* lut,
                           const uint16_t* scale, const uint16_t* offset,
-                          int64_t M, int64_t N, int64_t K, int bits, bool repacked,
+                          int64_t M, int64_t N, int64_t K, int bits, bool repacked, int cus,
                           uint16_t* y, void* workspace, hipStream_t stream) {
-    const int64_t gm = (M + PBM - 1) / PBM, gn = (N + PBN - 1) / PBN;
+    const PrefillPlan pp = plan_prefill(M, N, K, cus);
     const int64_t units = M * (K / kGroup);
     const int64_t sblocks = (units * 16 + 255) / 256;
-    if (gm > 0x7FFFFFFF || gn > 65535 || sblocks > 0x7FFFFFFF || K / kGroup > 0x1FFFFFFF) return hipErrorInvalidValue;
+    const int64_t nblocks = pp.tiles - pp.tail_tiles + pp.tail_tiles * pp.tail_s;
+    if (pp.gm > 0x7FFFFFFF || nblocks > 0x7FFFFFFF || sblocks > 0x7FFFFFFF || K / kGroup > 0x1FFFFFFF) return hipErrorInvalidValue;
     const int KP = prefill_kp(K);
     uint16_t* xsums = static_cast<uint16_t*>(workspace);
+    unsigned long long* counters = reinterpret_cast<unsigned long long*>(static_cast<char*>(workspace) + pp.xsums_bytes);
+    float* partial = reinterpret_cast<float*>(static_cast<char*>(workspace) + pp.xsums_bytes + pp.counter_bytes);
     hipLaunchKernelGGL(group_sums_kernel, dim3((unsigned)sblocks), dim3(256), 0, stream, x, M, K, KP, xsums);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const dim3 grid((unsigned)gm, (unsigned)gn), block(PTHREADS);
+    const dim3 grid((unsigned)nblocks), block(PTHREADS);
+    const int gm = (int)pp.gm, tail_first = (int)(pp.tiles - pp.tail_tiles), tail_s = pp.tail_s;
 #define ANY4_PREFILL(B)                                                                                           \
     do {                                                                                                          \
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(prefill_kernel<B>),                                 \
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)prefill_lds_bytes(B));           \
         if (e != hipSuccess) return e;                                                                            \
         hipLaunchKernelGGL(prefill_kernel<B>, grid, block, prefill_lds_bytes(B), stream, x, codes, lut, scale,    \
-                           offset, xsums, KP, M, N, K, repacked ? 1 : 0, y);                                                        \
+                           offset, xsums, KP, M, N, K, repacked ? 1 : 0, gm, tail_first, tail_s, counters, partial, y); \
     } while (0)
     switch (bits) {
         case 4: ANY4_PREFILL(4); break;

@@ -8,8 +8,7 @@
 // carry the tag (never-initialised memory, or memory an earlier call used for something else)
 // counts as zero arrivals, so the workspace needs no initialisation; the last block puts the
 // counter back to (tag, 0), so every completed call leaves its counters clean - for the next call
-// and for any number of replays of a captured launch.  The arrival itself is in
-// any4_decode_stream.hip.
+// and for any number of replays of a captured launch.
 #pragma once
 #include "any4_device.h"
 
@@ -29,6 +28,34 @@ __device__ __forceinline__ void splitk_store(float* p, float v) {
 }
 __device__ __forceinline__ float splitk_load(const float* p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// One arrival at a tile's counter by a single thread; true if this was the last of `ksplit`.
+// The caller has made its partial sums visible (stores issued and waited for) beforehand.
+// A counter word is (tag << 8 | arrivals).  The last arrival of a tile puts its counter back to
+// "tag, 0", so a workspace that has served a call is clean for the next one and an arrival is ONE
+// atomic add; a word without the tag (a workspace used for the first time, or memory that held
+// something else) is claimed with a compare-and-swap instead.
+constexpr unsigned long long kArriveTag = 0x00A4C0DE5EED17ull;          // 56 bits
+__device__ __forceinline__ bool arrive_one(unsigned long long* c, int ksplit) {
+    unsigned long long old = __hip_atomic_fetch_add(c, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    unsigned long long cnt;
+    if ((old >> 8) == kArriveTag) {
+        cnt = (old & 0xFFull) + 1ull;
+    } else {
+        // the add above went into a foreign word and is dropped with it
+        old += 1ull;
+        for (;;) {
+            cnt = ((old >> 8) == kArriveTag) ? (old & 0xFFull) + 1ull : 1ull;
+            const unsigned long long nv = (kArriveTag << 8) | cnt;
+            if (__hip_atomic_compare_exchange_strong(c, &old, nv, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                                                     __HIP_MEMORY_SCOPE_AGENT))
+                break;
+        }
+    }
+    const bool last = cnt == (unsigned long long)ksplit;
+    if (last) __hip_atomic_store(c, kArriveTag << 8, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return last;
 }
 
 }  // namespace any4
