@@ -217,6 +217,41 @@ def test_gemm_is_reproducible(any4, oracle):
         assert torch.equal(a, any4.any4_gemm(*args).view(torch.int16).cpu())
 
 
+def test_gemm_with_k_slices_on_the_matrix_cores_is_reproducible_and_graph_safe(any4, oracle):
+    """A problem of few tiles: the matrix-core kernel cuts them along K and the last slice to arrive
+    adds the partial sums in slice order, so the result does not depend on which block was last; the
+    arrival counters are left clean, so the same workspace serves replays of a captured launch."""
+    M, N, K = 300, 384, 4096
+    cs = inputs.make_case(M, N, K, 4, seed=21)
+    packed = oracle.pack(cs.codes_u8, 4)
+    codes = dev_codes(packed)
+    x, lut, sc, of = dev_bf16(cs.x), dev_bf16(cs.lut), dev_bf16(cs.scale), dev_bf16(cs.offset)
+    need = any4.any4_gemm_workspace_bytes(M, N, K, 4)
+    assert need > 6 * 256 * 128 * 4                                  # partial tiles of several slices
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda").fill_(0xA5)       # no initialisation expected
+    y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    a = any4.any4_gemm(x, codes, lut, sc, of, 4, out=y, workspace=ws).view(torch.int16).cpu().clone()
+    y64 = oracle.gemm(cs.x, packed, cs.lut, cs.scale, cs.offset, K, 4, threads=8)
+    check_gemm(y, y64, oracle.rms(y64), ("k slices", M, N, K))
+    for _ in range(3):
+        y.zero_()
+        any4.any4_gemm(x, codes, lut, sc, of, 4, out=y, workspace=ws)
+        assert torch.equal(a, y.view(torch.int16).cpu())
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        any4.any4_gemm(x, codes, lut, sc, of, 4, out=y, workspace=ws)          # warm-up on the capture stream
+        with torch.cuda.graph(g, stream=side):
+            any4.any4_gemm(x, codes, lut, sc, of, 4, out=y, workspace=ws)
+    torch.cuda.current_stream().wait_stream(side)
+    for _ in range(3):
+        y.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(a, y.view(torch.int16).cpu())
+
+
 def test_gemm_rejects_small_workspace_and_leaves_output_alone(any4):
     cs = inputs.make_case(4, 64, 16384, 4, seed=12)
     codes = any4.any4_pack(torch.from_numpy(cs.codes_u8).cuda(), 4)
