@@ -31,6 +31,8 @@
  * (nf4-style) equivalence, closed forms (one-hot table, constant codes, zero
  * table, unit-vector activations), reduction to a library fp64 matmul, pack /
  * unpack round trips, and the bits-per-weight figure printed in section 2.4.1.
+ * Group sizes other than 128 (the *_g functions): expanding the scales to one per 128 weights
+ * must give the 128-group result bit for bit, a single group per row has a closed form.
  * The tile-major re-layout (any4o_repack) is pinned by a word-level transpose written
  * with numpy, by reading single codes back out of it, by its zero padding and by the
  * multiset of its words.
@@ -124,18 +126,25 @@ int any4o_repack(const uint32_t *packed, int64_t N, int64_t K, int bits, uint32_
  * Returns the number of elements for which (v*s)+o, rounded after each step,
  * differs in bit pattern from the fused result (expected 0: a product of two bf16
  * numbers is exact in fp32), or -1 on bad arguments. */
-int64_t any4o_dequant(const uint32_t *packed, const uint16_t *lut, const uint16_t *scale,
-                      const uint16_t *offset, int64_t N, int64_t K, int bits, float *w) {
-    if (!packed || !lut || !scale || !offset || !w || N < 1 || K < 1 || K % ANY4O_GROUP || !bits_ok(bits))
+static int group_ok(int64_t K, int64_t group) {
+    return group >= ANY4O_GROUP && group % ANY4O_GROUP == 0 && K % group == 0;
+}
+
+/* the same with a group of `group` weights (a multiple of 128 that divides K; the paper's
+ * Table 4 varies the group size): scale / offset are [N][K / group] */
+int64_t any4o_dequant_g(const uint32_t *packed, const uint16_t *lut, const uint16_t *scale,
+                        const uint16_t *offset, int64_t N, int64_t K, int bits, int64_t group, float *w) {
+    if (!packed || !lut || !scale || !offset || !w || N < 1 || K < 1 || K % ANY4O_GROUP || !bits_ok(bits) ||
+        !group_ok(K, group))
         return -1;
-    int64_t W = any4o_row_words(K, bits), G = K / ANY4O_GROUP, L = 1 << bits;
+    int64_t W = any4o_row_words(K, bits), G = K / group, L = 1 << bits;
     int64_t differ = 0;
     for (int64_t n = 0; n < N; ++n) {
         for (int64_t k = 0; k < K; ++k) {
             uint32_t c = any4o_code(packed + n * W, k, bits);
             float v = bf16_bits_to_float(lut[n * L + c]);
-            float s = bf16_bits_to_float(scale[n * G + k / ANY4O_GROUP]);
-            float o = bf16_bits_to_float(offset[n * G + k / ANY4O_GROUP]);
+            float s = bf16_bits_to_float(scale[n * G + k / group]);
+            float o = bf16_bits_to_float(offset[n * G + k / group]);
             float fused = fmaf(v, s, o);
             volatile float prod = v * s;              /* force the intermediate rounding */
             volatile float two_step = prod + o;
@@ -147,15 +156,21 @@ int64_t any4o_dequant(const uint32_t *packed, const uint16_t *lut, const uint16_
     return differ;
 }
 
+int64_t any4o_dequant(const uint32_t *packed, const uint16_t *lut, const uint16_t *scale,
+                      const uint16_t *offset, int64_t N, int64_t K, int bits, float *w) {
+    return any4o_dequant_g(packed, lut, scale, offset, N, K, bits, ANY4O_GROUP, w);
+}
+
 /* y[m][n] = sum_{k=0..K-1} (double)w[n][k] * (double)x[m][k], k ascending, fp64.
  * `threads` > 1 only distributes whole output rows n over OpenMP threads; the
  * arithmetic of every output element is unchanged.  Returns 0 or -1. */
-int any4o_gemm(const uint16_t *x, const uint32_t *packed, const uint16_t *lut, const uint16_t *scale,
-               const uint16_t *offset, int64_t M, int64_t N, int64_t K, int bits, double *y, int threads) {
+int any4o_gemm_g(const uint16_t *x, const uint32_t *packed, const uint16_t *lut, const uint16_t *scale,
+                 const uint16_t *offset, int64_t M, int64_t N, int64_t K, int bits, int64_t group,
+                 double *y, int threads) {
     if (!x || !packed || !lut || !scale || !offset || !y || M < 1 || N < 1 || K < 1 ||
-        K % ANY4O_GROUP || !bits_ok(bits))
+        K % ANY4O_GROUP || !bits_ok(bits) || !group_ok(K, group))
         return -1;
-    int64_t W = any4o_row_words(K, bits), G = K / ANY4O_GROUP, L = 1 << bits;
+    int64_t W = any4o_row_words(K, bits), G = K / group, L = 1 << bits;
     if (threads < 1) threads = 1;
 #pragma omp parallel num_threads(threads)
     {
@@ -165,8 +180,8 @@ int any4o_gemm(const uint16_t *x, const uint32_t *packed, const uint16_t *lut, c
             for (int64_t k = 0; k < K; ++k) {
                 uint32_t c = any4o_code(packed + n * W, k, bits);
                 float v = bf16_bits_to_float(lut[n * L + c]);
-                float s = bf16_bits_to_float(scale[n * G + k / ANY4O_GROUP]);
-                float o = bf16_bits_to_float(offset[n * G + k / ANY4O_GROUP]);
+                float s = bf16_bits_to_float(scale[n * G + k / group]);
+                float o = bf16_bits_to_float(offset[n * G + k / group]);
                 wrow[k] = fmaf(v, s, o);
             }
             for (int64_t m = 0; m < M; ++m) {
@@ -179,6 +194,11 @@ int any4o_gemm(const uint16_t *x, const uint32_t *packed, const uint16_t *lut, c
         free(wrow);
     }
     return 0;
+}
+
+int any4o_gemm(const uint16_t *x, const uint32_t *packed, const uint16_t *lut, const uint16_t *scale,
+               const uint16_t *offset, int64_t M, int64_t N, int64_t K, int bits, double *y, int threads) {
+    return any4o_gemm_g(x, packed, lut, scale, offset, M, N, K, bits, ANY4O_GROUP, y, threads);
 }
 
 /* root mean square of n doubles */

@@ -46,6 +46,10 @@ def _load():
         lib.any4o_dequant.argtypes = [p, p, p, p, i64, i64, ctypes.c_int, p]
         lib.any4o_gemm.restype = ctypes.c_int
         lib.any4o_gemm.argtypes = [p, p, p, p, p, i64, i64, i64, ctypes.c_int, p, ctypes.c_int]
+        lib.any4o_dequant_g.restype = i64
+        lib.any4o_dequant_g.argtypes = [p, p, p, p, i64, i64, ctypes.c_int, i64, p]
+        lib.any4o_gemm_g.restype = ctypes.c_int
+        lib.any4o_gemm_g.argtypes = [p, p, p, p, p, i64, i64, i64, ctypes.c_int, i64, p, ctypes.c_int]
         lib.any4o_rms.restype = ctypes.c_double
         lib.any4o_rms.argtypes = [p, i64]
         lib.any4o_bits_per_weight.restype = ctypes.c_double
@@ -104,23 +108,25 @@ def unpack(packed: np.ndarray, K: int, bits: int) -> np.ndarray:
     return out
 
 
-def dequant(packed, lut, scale, offset, K: int, bits: int, return_differ: bool = False):
+def dequant(packed, lut, scale, offset, K: int, bits: int, return_differ: bool = False, group: int = GROUP):
     """fp32 [N,K] dequantised weights; optionally also the count of elements whose
-    fused and two-step roundings differ (expected 0)."""
+    fused and two-step roundings differ (expected 0).  scale / offset are [N, K / group]."""
     N = packed.shape[0]
     a, pa = _c(packed, np.uint32)
     b, pb = _c(lut, np.uint16)
     c, pc = _c(scale, np.uint16)
     d, pd = _c(offset, np.uint16)
     w = np.empty((N, K), dtype=np.float32)
-    differ = _load().any4o_dequant(pa, pb, pc, pd, N, K, bits, w.ctypes.data_as(ctypes.c_void_p))
+    if c.shape != (N, K // group) or d.shape != (N, K // group):
+        raise ValueError("scale / offset must be [N, K / group]")
+    differ = _load().any4o_dequant_g(pa, pb, pc, pd, N, K, bits, group, w.ctypes.data_as(ctypes.c_void_p))
     if differ < 0:
         raise ValueError("any4o_dequant: bad arguments")
     return (w, int(differ)) if return_differ else w
 
 
-def gemm(x, packed, lut, scale, offset, K: int, bits: int, threads: int = 1) -> np.ndarray:
-    """fp64 [M,N] = x[M,K] . dequant(...)[N,K]^T, sequential in k."""
+def gemm(x, packed, lut, scale, offset, K: int, bits: int, threads: int = 1, group: int = GROUP) -> np.ndarray:
+    """fp64 [M,N] = x[M,K] . dequant(...)[N,K]^T, sequential in k.  scale / offset are [N, K / group]."""
     N = packed.shape[0]
     M = x.shape[0]
     xx, px = _c(x, np.uint16)
@@ -129,7 +135,9 @@ def gemm(x, packed, lut, scale, offset, K: int, bits: int, threads: int = 1) -> 
     c, pc = _c(scale, np.uint16)
     d, pd = _c(offset, np.uint16)
     y = np.empty((M, N), dtype=np.float64)
-    rc = _load().any4o_gemm(px, pa, pb, pc, pd, M, N, K, bits, y.ctypes.data_as(ctypes.c_void_p), threads)
+    if c.shape != (N, K // group) or d.shape != (N, K // group):
+        raise ValueError("scale / offset must be [N, K / group]")
+    rc = _load().any4o_gemm_g(px, pa, pb, pc, pd, M, N, K, bits, group, y.ctypes.data_as(ctypes.c_void_p), threads)
     if rc != 0:
         raise ValueError("any4o_gemm: bad arguments")
     return y

@@ -1,0 +1,62 @@
+"""Pins of the oracle's group-size parameter (any4o_dequant_g / any4o_gemm_g).  The paper shares a
+scale and an offset among g consecutive weights along K (section 2.5.1, "Groupwise") and varies g
+in its ablation (Table 4); the library's default and the GEMM's native chunk is g = 128."""
+import numpy as np
+import pytest
+
+from paper_2507_04610_amd import inputs
+
+
+def case(N, K, bits, group, seed):
+    cs = inputs.make_case(3, N, K, bits, seed)
+    r = group // 128
+    return cs, np.ascontiguousarray(cs.scale[:, ::r]), np.ascontiguousarray(cs.offset[:, ::r])
+
+
+@pytest.mark.parametrize("bits", (4, 3, 2))
+@pytest.mark.parametrize("group", (128, 256, 512, 1024))
+def test_coarser_groups_equal_repeated_scales(oracle, bits, group):
+    """One scale per `group` weights is the same function as that scale repeated for every 128
+    weights of the group: both routes must agree bit for bit (dequant) and exactly (fp64 GEMM)."""
+    N, K = 7, 2048
+    cs, sc, of = case(N, K, bits, group, 3)
+    packed = oracle.pack(cs.codes_u8, bits)
+    r = group // 128
+    sc128, of128 = np.repeat(sc, r, axis=1), np.repeat(of, r, axis=1)
+    w_g = oracle.dequant(packed, cs.lut, sc, of, K, bits, group=group)
+    w_128 = oracle.dequant(packed, cs.lut, sc128, of128, K, bits)
+    assert np.array_equal(w_g.view(np.uint32), w_128.view(np.uint32))
+    y_g = oracle.gemm(cs.x, packed, cs.lut, sc, of, K, bits, group=group)
+    y_128 = oracle.gemm(cs.x, packed, cs.lut, sc128, of128, K, bits)
+    assert np.array_equal(y_g, y_128)
+
+
+def test_one_group_per_row_has_a_closed_form(oracle):
+    """group = K: y[m][n] = s_n * sum_k x LUT[code] + o_n * sum_k x, up to the fp32 rounding of each
+    weight (with bf16 inputs of similar magnitude most weights are exact in fp32, and so are the
+    fp64 sums: the two sides usually agree to the last bit)."""
+    N, K, bits = 5, 1024, 4
+    cs, sc, of = case(N, K, bits, 1024, 5)
+    packed = oracle.pack(cs.codes_u8, bits)
+    y = oracle.gemm(cs.x, packed, cs.lut, sc, of, K, bits, group=1024)
+    lut = inputs.bf16_bits_to_f32(cs.lut).astype(np.float64)
+    x = inputs.bf16_bits_to_f32(cs.x).astype(np.float64)
+    v = np.take_along_axis(lut, cs.codes_u8.astype(np.int64), axis=1)            # [N, K]
+    s = inputs.bf16_bits_to_f32(sc).astype(np.float64)[:, 0]
+    o = inputs.bf16_bits_to_f32(of).astype(np.float64)[:, 0]
+    want = (x @ v.T) * s[None, :] + x.sum(axis=1)[:, None] * o[None, :]
+    scale_of_terms = (np.abs(x) @ np.abs(v).T) * np.abs(s)[None, :] + np.abs(x).sum(axis=1)[:, None] * np.abs(o)[None, :]
+    assert np.all(np.abs(y - want) <= 2.0 ** -23 * scale_of_terms)
+    # and the grouping matters: with the scales of another row the result is far off
+    other = oracle.gemm(cs.x, packed, cs.lut, np.roll(sc, 1, axis=0), of, K, bits, group=1024)
+    assert np.abs(other - want).max() > 1e-3 * np.abs(want).max()
+
+
+def test_group_must_divide_k_and_be_a_multiple_of_128(oracle):
+    cs, sc, of = case(4, 1024, 4, 256, 1)
+    packed = oracle.pack(cs.codes_u8, 4)
+    for bad in (64, 192, 768, 2048):
+        with pytest.raises(ValueError):
+            oracle.dequant(packed, cs.lut, sc, of, 1024, 4, group=bad)
+    with pytest.raises(ValueError):
+        oracle.gemm(cs.x, packed, cs.lut, cs.scale, cs.offset, 1024, 4, group=256)   # wrong shape for the group
