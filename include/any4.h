@@ -102,6 +102,26 @@ int any4_gemm(const uint16_t* x, const uint32_t* codes, const uint16_t* lut,
 size_t any4_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int bits);
 
 /*
+ * any4_dequant_grouped / any4_gemm_grouped - the same two operations with a scale and an offset
+ * shared by `group` consecutive weights along K instead of 128 (section 2.5.1, "Groupwise"; the
+ * paper's Table 4 varies the group size): scale and offset are bf16 [N][K/group].
+ *   group   128, 256, 512 or 1024, and a divisor of K; anything else returns ANY4_ERR_SHAPE
+ *           (a group of 64 is not supported: the small-M kernel's matrix instruction sums over
+ *           128 weights at a time).
+ * Every other argument, the workspace size (any4_gemm_workspace_bytes) and the error behaviour
+ * are those of any4_dequant / any4_gemm; with group = 128 the calls are identical to them.
+ * any4_gemm_grouped needs a table (lut != NULL) unless group = 128.
+ * For M <= 16, K > 262144 is served for group = 128 only (ANY4_ERR_SHAPE otherwise).
+ */
+int any4_dequant_grouped(const uint32_t* codes, const uint16_t* lut, const uint16_t* scale,
+                         const uint16_t* offset, int64_t N, int64_t K, int bits, int group,
+                         float* w, void* stream);
+int any4_gemm_grouped(const uint16_t* x, const uint32_t* codes, const uint16_t* lut,
+                      const uint16_t* scale, const uint16_t* offset,
+                      int64_t M, int64_t N, int64_t K, int bits, int group,
+                      uint16_t* y, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * any4_repack - re-arrange packed codes offline into the order the kernels read them in.
  * The paper stores the weights in the operand order of the matrix instruction so that a lane's
  * load needs no shuffling (section 4.2, second paragraph).  On this GPU the row-major layout

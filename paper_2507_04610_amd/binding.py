@@ -16,7 +16,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libany4.so")
 GROUP = 128
 
-EXPORTS = ("any4_pack", "any4_dequant", "any4_gemm", "any4_gemm_workspace_bytes", "any4_repack", "any4_repack_bytes", "any4_gemm_repacked",
+EXPORTS = ("any4_pack", "any4_dequant", "any4_gemm", "any4_gemm_workspace_bytes", "any4_repack", "any4_repack_bytes", "any4_gemm_repacked", "any4_dequant_grouped", "any4_gemm_grouped",
            "any4_quantize", "any4_quantize_max_k", "any4_stream_read", "any4_strerror", "any4_version")
 
 
@@ -45,6 +45,10 @@ def load_library() -> ctypes.CDLL:
     lib.any4_gemm.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, ci, vp, vp, ctypes.c_size_t, vp]
     lib.any4_gemm_workspace_bytes.restype = ctypes.c_size_t
     lib.any4_gemm_workspace_bytes.argtypes = [i64, i64, i64, ci]
+    lib.any4_dequant_grouped.restype = ci
+    lib.any4_dequant_grouped.argtypes = [vp, vp, vp, vp, i64, i64, ci, ci, vp, vp]
+    lib.any4_gemm_grouped.restype = ci
+    lib.any4_gemm_grouped.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, ci, ci, vp, vp, ctypes.c_size_t, vp]
     lib.any4_gemm_repacked.restype = ci
     lib.any4_gemm_repacked.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, ci, vp, vp, ctypes.c_size_t, vp]
     lib.any4_repack.restype = ci
@@ -114,8 +118,9 @@ def any4_pack(codes_u8: torch.Tensor, bits: int = 4, out: torch.Tensor | None = 
 
 
 def any4_dequant(codes: torch.Tensor, lut: torch.Tensor | None, scale: torch.Tensor, offset: torch.Tensor,
-                 K: int, bits: int = 4, out: torch.Tensor | None = None) -> torch.Tensor:
-    """fp32 [N,K] dequantised weights (lut None with bits 4: the int4 grid, value = code - 8)."""
+                 K: int, bits: int = 4, out: torch.Tensor | None = None, group: int = GROUP) -> torch.Tensor:
+    """fp32 [N,K] dequantised weights (lut None with bits 4: the int4 grid, value = code - 8);
+    scale / offset are [N, K / group] (any4_dequant_grouped when group is not 128)."""
     lib = load_library()
     N = codes.shape[0]
     pc = _dev(codes, torch.int32, "codes")
@@ -125,11 +130,14 @@ def any4_dequant(codes: torch.Tensor, lut: torch.Tensor | None, scale: torch.Ten
     if out is None:
         out = torch.empty((N, K), dtype=torch.float32, device=codes.device)
     pw = _dev(out, torch.float32, "out")
-    _check(lib.any4_dequant(pc, pl, ps, po, N, K, bits, pw, _stream()), "any4_dequant")
+    if group == GROUP:
+        _check(lib.any4_dequant(pc, pl, ps, po, N, K, bits, pw, _stream()), "any4_dequant")
+    else:
+        _check(lib.any4_dequant_grouped(pc, pl, ps, po, N, K, bits, group, pw, _stream()), "any4_dequant_grouped")
     return out
 
 
-def _gemm(entry: str, x, codes, N, lut, scale, offset, bits, out, workspace):
+def _gemm(entry: str, x, codes, N, lut, scale, offset, bits, out, workspace, group=None):
     lib = load_library()
     M, K = x.shape
     px = _dev(x, torch.bfloat16, "x")
@@ -145,16 +153,22 @@ def _gemm(entry: str, x, codes, N, lut, scale, offset, bits, out, workspace):
         workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
     pw = workspace.data_ptr() if workspace is not None else None
     wbytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
-    _check(getattr(lib, entry)(px, pc, pl, ps, po, M, N, K, bits, py, pw, wbytes, _stream()), entry)
+    if group is None:
+        _check(getattr(lib, entry)(px, pc, pl, ps, po, M, N, K, bits, py, pw, wbytes, _stream()), entry)
+    else:
+        _check(getattr(lib, entry)(px, pc, pl, ps, po, M, N, K, bits, group, py, pw, wbytes, _stream()), entry)
     return out
 
 
 def any4_gemm(x: torch.Tensor, codes: torch.Tensor, lut: torch.Tensor | None, scale: torch.Tensor,
               offset: torch.Tensor, bits: int = 4, out: torch.Tensor | None = None,
-              workspace: torch.Tensor | None = None) -> torch.Tensor:
+              workspace: torch.Tensor | None = None, group: int = GROUP) -> torch.Tensor:
     """bf16 [M,N] = x[M,K] . dequant(codes, lut, scale, offset)[N,K]^T
-    (lut None with bits 4: the int4 grid, value = code - 8, run without a table)."""
-    return _gemm("any4_gemm", x, codes, codes.shape[0], lut, scale, offset, bits, out, workspace)
+    (lut None with bits 4: the int4 grid, value = code - 8, run without a table);
+    scale / offset are [N, K / group] (any4_gemm_grouped when group is not 128)."""
+    if group == GROUP:
+        return _gemm("any4_gemm", x, codes, codes.shape[0], lut, scale, offset, bits, out, workspace)
+    return _gemm("any4_gemm_grouped", x, codes, codes.shape[0], lut, scale, offset, bits, out, workspace, group)
 
 
 def any4_repack_bytes(N: int, K: int, bits: int = 4) -> int:

@@ -14,6 +14,13 @@ static int shape_check(int64_t N, int64_t K, int bits) {
     return ANY4_OK;
 }
 
+// log2(group / 128) for the group sizes the kernels take (a multiple of 128 that divides K), else -1
+static int group_shift(int64_t K, int group) {
+    for (int lr = 0; lr <= 3; ++lr)
+        if (group == (ANY4_GROUP << lr)) return K % group == 0 ? lr : -1;
+    return -1;
+}
+
 constexpr int kDecodeMaxM = 16;
 constexpr int kStreamMaxM = 16;
 constexpr int kChunkedMaxM = 128;      // above this the matrix-core kernel is always taken
@@ -107,15 +114,23 @@ int any4_pack(const uint8_t* codes_u8, int64_t N, int64_t K, int bits, uint32_t*
                ? ANY4_OK : ANY4_ERR_HIP;
 }
 
-int any4_dequant(const uint32_t* codes, const uint16_t* lut, const uint16_t* scale,
-                 const uint16_t* offset, int64_t N, int64_t K, int bits, float* w, void* stream) {
+int any4_dequant_grouped(const uint32_t* codes, const uint16_t* lut, const uint16_t* scale,
+                         const uint16_t* offset, int64_t N, int64_t K, int bits, int group, float* w,
+                         void* stream) {
     if (!codes || !scale || !offset || !w) return ANY4_ERR_NULL;
     if (!lut && bits != 4) return ANY4_ERR_NULL;           // no table = the 4-bit integer grid only
     if (int rc = shape_check(N, K, bits)) return rc;
+    const int lr = group_shift(K, group);
+    if (lr < 0) return ANY4_ERR_SHAPE;
     if (!aligned16(codes) || !aligned16(lut) || !aligned16(scale) || !aligned16(offset) || !aligned16(w))
         return ANY4_ERR_ALIGN;
-    return launch_dequant(codes, lut, scale, offset, N, K, bits, w, static_cast<hipStream_t>(stream)) == hipSuccess
+    return launch_dequant(codes, lut, scale, offset, N, K, bits, lr, w, static_cast<hipStream_t>(stream)) == hipSuccess
                ? ANY4_OK : ANY4_ERR_HIP;
+}
+
+int any4_dequant(const uint32_t* codes, const uint16_t* lut, const uint16_t* scale,
+                 const uint16_t* offset, int64_t N, int64_t K, int bits, float* w, void* stream) {
+    return any4_dequant_grouped(codes, lut, scale, offset, N, K, bits, ANY4_GROUP, w, stream);
 }
 
 int any4_stream_read(const void* p, size_t bytes, uint32_t magic, uint32_t* sink, void* stream) {
@@ -149,16 +164,20 @@ size_t any4_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int bits) {
 
 static int gemm_any_layout(const uint16_t* x, const uint32_t* codes, bool repacked, const uint16_t* lut,
                            const uint16_t* scale, const uint16_t* offset, int64_t M, int64_t N, int64_t K,
-                           int bits, uint16_t* y, void* workspace, size_t workspace_bytes, void* stream) {
+                           int bits, int group, uint16_t* y, void* workspace, size_t workspace_bytes, void* stream) {
     if (!x || !codes || !scale || !offset || !y) return ANY4_ERR_NULL;
     if (!lut && (bits != 4 || repacked)) return ANY4_ERR_NULL;       // no table = the 4-bit integer grid, plain layout only
     if (int rc = shape_check(N, K, bits)) return rc;
     if (M < 1) return ANY4_ERR_SHAPE;
+    const int lr = group_shift(K, group);
+    if (lr < 0) return ANY4_ERR_SHAPE;
+    if (!lut && lr > 0) return ANY4_ERR_NULL;                            // the table-free path has groups of 128
     if (!aligned16(x) || !aligned16(codes) || !aligned16(lut) || !aligned16(scale) ||
         !aligned16(offset) || !aligned16(y) || !aligned16(workspace))
         return ANY4_ERR_ALIGN;
     const GemmPlan plan = plan_gemm(M, N, K, bits);
-    if (repacked && plan.decode && !plan.stream) return ANY4_ERR_SHAPE;   // K beyond the streaming kernel's range
+    // K beyond the streaming kernel's range: only the plain layout with groups of 128
+    if ((repacked || lr > 0) && plan.decode && !plan.stream) return ANY4_ERR_SHAPE;
     if (plan.workspace > 0 && (!workspace || workspace_bytes < plan.workspace)) return ANY4_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t e;
@@ -167,15 +186,15 @@ static int gemm_any_layout(const uint16_t* x, const uint32_t* codes, bool repack
         e = hipSuccess;
         for (int64_t m0 = 0; m0 < M && e == hipSuccess; m0 += kStreamMaxM) {
             const int64_t rows = M - m0 < kStreamMaxM ? M - m0 : kStreamMaxM;
-            e = launch_decode_stream(x + m0 * K, codes, lut, scale, offset, rows, N, K, bits, repacked,
+            e = launch_decode_stream(x + m0 * K, codes, lut, scale, offset, rows, N, K, bits, lr, repacked,
                                      rows == kStreamMaxM ? plan.sp : plan.sp_tail, y + m0 * N, workspace, s);
         }
     } else if (plan.stream) {
-        e = launch_decode_stream(x, codes, lut, scale, offset, M, N, K, bits, repacked, plan.sp, y, workspace, s);
+        e = launch_decode_stream(x, codes, lut, scale, offset, M, N, K, bits, lr, repacked, plan.sp, y, workspace, s);
     } else if (plan.decode) {
         e = launch_decode(x, codes, lut, scale, offset, M, N, K, bits, plan, y, static_cast<float*>(workspace), s);
     } else {
-        e = launch_prefill(x, codes, lut, scale, offset, M, N, K, bits, repacked, device_compute_units(), y, workspace, s);
+        e = launch_prefill(x, codes, lut, scale, offset, M, N, K, bits, lr, repacked, device_compute_units(), y, workspace, s);
     }
     return e == hipSuccess ? ANY4_OK : ANY4_ERR_HIP;
 }
@@ -183,13 +202,19 @@ static int gemm_any_layout(const uint16_t* x, const uint32_t* codes, bool repack
 int any4_gemm(const uint16_t* x, const uint32_t* codes, const uint16_t* lut, const uint16_t* scale,
               const uint16_t* offset, int64_t M, int64_t N, int64_t K, int bits, uint16_t* y,
               void* workspace, size_t workspace_bytes, void* stream) {
-    return gemm_any_layout(x, codes, false, lut, scale, offset, M, N, K, bits, y, workspace, workspace_bytes, stream);
+    return gemm_any_layout(x, codes, false, lut, scale, offset, M, N, K, bits, ANY4_GROUP, y, workspace, workspace_bytes, stream);
+}
+
+int any4_gemm_grouped(const uint16_t* x, const uint32_t* codes, const uint16_t* lut, const uint16_t* scale,
+                      const uint16_t* offset, int64_t M, int64_t N, int64_t K, int bits, int group, uint16_t* y,
+                      void* workspace, size_t workspace_bytes, void* stream) {
+    return gemm_any_layout(x, codes, false, lut, scale, offset, M, N, K, bits, group, y, workspace, workspace_bytes, stream);
 }
 
 int any4_gemm_repacked(const uint16_t* x, const uint32_t* rcodes, const uint16_t* lut, const uint16_t* scale,
                        const uint16_t* offset, int64_t M, int64_t N, int64_t K, int bits, uint16_t* y,
                        void* workspace, size_t workspace_bytes, void* stream) {
-    return gemm_any_layout(x, rcodes, true, lut, scale, offset, M, N, K, bits, y, workspace, workspace_bytes, stream);
+    return gemm_any_layout(x, rcodes, true, lut, scale, offset, M, N, K, bits, ANY4_GROUP, y, workspace, workspace_bytes, stream);
 }
 
 size_t any4_repack_bytes(int64_t N, int64_t K, int bits) {

@@ -112,6 +112,8 @@ struct Params {
     unsigned long long* counters;    // [tiles], slabs > 1 only
     int64_t N, K;
     int M, G;                        // G = K / 128
+    int lr;                          // log2(group size / 128): chunk g of 128 weights reads scale / offset g >> lr
+                                     // of its row (rows of G >> lr entries)
     int slabs, slab_groups;          // groups per slab (the last slab may have fewer)
     int blocks_per_slab, tiles;
 #ifdef ANY4_TUNING
@@ -142,8 +144,9 @@ __device__ __forceinline__ float sum8(const uint4& v) {
 //         A code c becomes the bf16 number 128 + c by OR-ing it into the mantissa of 128.0
 //         (0x4300 | c), and the surplus 136 * scale * (group sum of x) is taken off again by two more
 //         exact bf16 terms (-128 * scale and -8 * scale) that ride in the offset MFMA.
-template <int BITS, int GW, bool AUX, bool NOLUT, bool REPACK>
+template <int BITS, int GW, bool AUX, bool NOLUT, bool REPACK, bool COARSE>
 __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Params p) {
+    static_assert(!COARSE || (!NOLUT && !REPACK), "groups above 128 weights: table-based, plain layout");
     static_assert(!NOLUT || BITS == 4, "the table-free path is the 4-bit integer grid");
     static_assert(!(NOLUT && REPACK), "the table-free path reads the plain layout only");
     static_assert(BITS == 4 || BITS == 3 || BITS == 2, "code width");
@@ -197,7 +200,8 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
     const uint32_t row_bytes = (uint32_t)(K * BITS / 8);
     const uint32_t vc_norm = (uint32_t)n * row_bytes + (uint32_t)q * QB, vc_last = (uint32_t)nc * row_bytes + (uint32_t)q * QB;
     const uint32_t vl_norm = (uint32_t)n * LUTB, vl_last = (uint32_t)nc * LUTB;
-    const uint32_t vs_norm = (uint32_t)n * (uint32_t)G * 2u, vs_last = (uint32_t)nc * (uint32_t)G * 2u;
+    const int lr = COARSE ? p.lr : 0, GS = G >> lr;      // scales / offsets per row
+    const uint32_t vs_norm = (uint32_t)n * (uint32_t)GS * 2u, vs_last = (uint32_t)nc * (uint32_t)GS * 2u;
     const char* const codes_b = reinterpret_cast<const char*>(p.codes);
     const char* const lut_b = reinterpret_cast<const char*>(p.lut);
     const char* const scale_b = reinterpret_cast<const char*>(p.scale);
@@ -303,27 +307,53 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
     uint2 axs[2], axo[2];
     uint4 axl;
     auto aux_load = [&](int t) {
-        const int64_t tile_off = (int64_t)t * (kTile * 2) * G + gs0 * 2;
-        const uint32_t vs = (t == last_tile ? vs_last : vs_norm) + (uint32_t)q * 8u;
+        if constexpr (!COARSE) {
+            // lanes past the slab's groups repeat its last four: the loads are unconditional
+            const int64_t tile_off = (int64_t)t * (kTile * 2) * G + gs0 * 2;
+            const uint32_t vs = t == last_tile ? vs_last : vs_norm;
 #pragma unroll
-        for (int c = 0; c < 2; ++c)
-            if ((c * 4 + q) * 4 < sg) {
-                axs[c] = *reinterpret_cast<const uint2*>(scale_b + tile_off + c * 32 + vs);
-                axo[c] = *reinterpret_cast<const uint2*>(offset_b + tile_off + c * 32 + vs);
+            for (int c = 0; c < 2; ++c) {
+                const uint32_t go = (uint32_t)min((c * 4 + q) * 4, max(sg, 4) - 4) * 2u;
+                axs[c] = *reinterpret_cast<const uint2*>(scale_b + tile_off + vs + go);
+                axo[c] = *reinterpret_cast<const uint2*>(offset_b + tile_off + vs + go);
             }
+        } else {
+            // groups of 256 weights and more: chunks 4j, 4j + 1 share a scale and so do 4j + 2, 4j + 3
+            // (4j is a multiple of 4), so two 2-byte loads give the four entries the slot expects.
+            // Lanes past the slab's groups repeat its last four chunks: all loads are unconditional.
+            const int64_t tile_off = (int64_t)t * (kTile * 2) * GS;
+            const uint32_t v = t == last_tile ? vs_last : vs_norm;
+            // The registers keep the bare values; they are doubled up when the slot is written.
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                const int g0 = gs0 + min((c * 4 + q) * 4, max(sg, 4) - 4);
+                const uint32_t i0 = (uint32_t)(g0 >> lr) * 2u, i1 = (uint32_t)((g0 + 2) >> lr) * 2u;
+                axs[c].x = *reinterpret_cast<const uint16_t*>(scale_b + tile_off + v + i0);
+                axs[c].y = *reinterpret_cast<const uint16_t*>(scale_b + tile_off + v + i1);
+                axo[c].x = *reinterpret_cast<const uint16_t*>(offset_b + tile_off + v + i0);
+                axo[c].y = *reinterpret_cast<const uint16_t*>(offset_b + tile_off + v + i1);
+            }
+        }
         const char* lrow = lut_b + (int64_t)t * (kTile * LUTB) + (t == last_tile ? vl_last : vl_norm);
         if constexpr (NOLUT) { (void)lrow; }
-        else if constexpr (BITS == 4) { if (q < 2) axl = *reinterpret_cast<const uint4*>(lrow + q * 16); }
-        else if constexpr (BITS == 3) { if (q < 1) axl = *reinterpret_cast<const uint4*>(lrow); }
-        else { if (q < 1) { const uint2 v = *reinterpret_cast<const uint2*>(lrow); axl.x = v.x; axl.y = v.y; } }
+        // (every lane loads, also those whose copy is not written to the slot: a load under a per-lane
+        // condition is waited for on the spot, together with all the code loads in flight)
+        else if constexpr (BITS == 4) { axl = *reinterpret_cast<const uint4*>(lrow + (q & 1) * 16); }
+        else if constexpr (BITS == 3) { axl = *reinterpret_cast<const uint4*>(lrow); }
+        else { const uint2 v = *reinterpret_cast<const uint2*>(lrow); axl.x = v.x; axl.y = v.y; }
     };
     auto aux_write = [&](int slot) {
         unsigned char* s = aux + slot * kAuxSlot;
 #pragma unroll
         for (int c = 0; c < 2; ++c)
             if ((c * 4 + q) * 4 < sg) {
-                *reinterpret_cast<uint2*>(s + kAuxScale + n * kAuxRow + (c * 4 + q) * 8) = axs[c];
-                *reinterpret_cast<uint2*>(s + kAuxOffset + n * kAuxRow + (c * 4 + q) * 8) = axo[c];
+                uint2 sv = axs[c], ov = axo[c];
+                if constexpr (COARSE) {
+                    sv = make_uint2(sv.x | (sv.x << 16), sv.y | (sv.y << 16));
+                    ov = make_uint2(ov.x | (ov.x << 16), ov.y | (ov.y << 16));
+                }
+                *reinterpret_cast<uint2*>(s + kAuxScale + n * kAuxRow + (c * 4 + q) * 8) = sv;
+                *reinterpret_cast<uint2*>(s + kAuxOffset + n * kAuxRow + (c * 4 + q) * 8) = ov;
             }
         if constexpr (NOLUT) { }
         else if constexpr (BITS == 4) { if (q < 2) *reinterpret_cast<uint4*>(s + kAuxLut + n * 32 + q * 16) = axl; }
@@ -358,12 +388,12 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
     uint32_t sraw[kDepth][GW], oraw[kDepth][GW];
     LutSrc lut_ring[kDepth];
     auto load_so = [&](uint32_t (&sr)[GW], uint32_t (&orw)[GW], int t) {
-        const int64_t tile_off = (int64_t)t * (kTile * 2) * G;
+        const int64_t tile_off = (int64_t)t * (kTile * 2) * GS;
         const uint32_t v = t == last_tile ? vs_last : vs_norm;
 #pragma unroll
         for (int gi = 0; gi < GW; ++gi) {
-            sr[gi] = *reinterpret_cast<const uint16_t*>(scale_b + tile_off + group_of(gi) * 2 + v);
-            orw[gi] = *reinterpret_cast<const uint16_t*>(offset_b + tile_off + group_of(gi) * 2 + v);
+            sr[gi] = *reinterpret_cast<const uint16_t*>(scale_b + tile_off + (group_of(gi) >> lr) * 2 + v);
+            orw[gi] = *reinterpret_cast<const uint16_t*>(offset_b + tile_off + (group_of(gi) >> lr) * 2 + v);
         }
     };
     auto pack_so = [&](uint32_t (&sp)[NP], uint32_t (&op)[NP], const uint32_t (&sr)[GW], const uint32_t (&orw)[GW]) {
@@ -845,9 +875,9 @@ StreamPlan plan_stream(int64_t M, int64_t N, int64_t K, int cus) {
     return best;
 }
 
-template <int BITS, int GW, bool AUX, bool NOLUT = false, bool REPACK = false>
+template <int BITS, int GW, bool AUX, bool NOLUT = false, bool REPACK = false, bool COARSE = false>
 static hipError_t launch_stream_t(const Params& p, int grid, hipStream_t stream) {
-    auto kern = stream::decode_stream_kernel<BITS, GW, AUX, NOLUT, REPACK>;
+    auto kern = stream::decode_stream_kernel<BITS, GW, AUX, NOLUT, REPACK, COARSE>;
 #ifdef ANY4_STAMPS
     constexpr int lds = stream::lds_bytes(BITS) + stream::kWaves * stream::kStampSteps * 4 * 8;
 #else
@@ -875,14 +905,15 @@ static hipError_t launch_stream_b(const Params& p, const StreamPlan& sp, int gri
 
 hipError_t launch_decode_stream(const uint16_t* x, const uint32_t* codes, const uint16_t* lut,
                                 const uint16_t* scale, const uint16_t* offset, int64_t M, int64_t N,
-                                int64_t K, int bits, bool repacked, const StreamPlan& sp, uint16_t* y,
+                                int64_t K, int bits, int lr, bool repacked, const StreamPlan& sp_in, uint16_t* y,
                                 void* workspace, hipStream_t stream) {
+    const StreamPlan& sp = sp_in;
     Params p{};
     p.x = x; p.codes = codes; p.lut = lut; p.scale = scale; p.offset = offset; p.y = y;
     p.counters = static_cast<unsigned long long*>(workspace);
     p.partial = sp.slabs > 1
         ? reinterpret_cast<float*>(static_cast<char*>(workspace) + splitk_counter_bytes(sp.tiles)) : nullptr;
-    p.N = N; p.K = K; p.M = (int)M; p.G = (int)(K / kGroup);
+    p.N = N; p.K = K; p.M = (int)M; p.G = (int)(K / kGroup); p.lr = lr;
     p.slabs = sp.slabs; p.slab_groups = sp.slab_groups; p.blocks_per_slab = sp.blocks_per_slab;
     p.tiles = (int)sp.tiles;
 #ifdef ANY4_TUNING
@@ -890,7 +921,7 @@ hipError_t launch_decode_stream(const uint16_t* x, const uint32_t* codes, const 
 #endif
     const int grid = sp.slabs * sp.blocks_per_slab;
     if (bits == 4 && lut == nullptr) {                     // the integer grid: no table
-        if (repacked) return hipErrorInvalidValue;
+        if (repacked || lr > 0) return hipErrorInvalidValue;
 #define ANY4_STREAM_NL(GW)                                                                 \
     (sp.aux ? launch_stream_t<4, GW, true, true>(p, grid, stream) : launch_stream_t<4, GW, false, true>(p, grid, stream))
         switch (sp.gw) {
@@ -899,6 +930,24 @@ hipError_t launch_decode_stream(const uint16_t* x, const uint32_t* codes, const 
             default: return ANY4_STREAM_NL(1);
         }
 #undef ANY4_STREAM_NL
+    }
+    if (lr > 0) {
+        // groups of 256 weights and more: the variants that read one scale per group
+        if (repacked) return hipErrorInvalidValue;
+#define ANY4_STREAM_C(B, GW)                                                               \
+        return sp.aux ? launch_stream_t<B, GW, true, false, false, true>(p, grid, stream)  \
+                      : launch_stream_t<B, GW, false, false, false, true>(p, grid, stream)
+#define ANY4_STREAM_CB(B)                                                                  \
+        switch (sp.gw) {                                                                   \
+            case 4: ANY4_STREAM_C(B, 4);                                                   \
+            case 2: ANY4_STREAM_C(B, 2);                                                   \
+            default: ANY4_STREAM_C(B, 1);                                                  \
+        }
+        if (bits == 4) { ANY4_STREAM_CB(4) }
+        if (bits == 3) { ANY4_STREAM_CB(3) }
+        ANY4_STREAM_CB(2)
+#undef ANY4_STREAM_CB
+#undef ANY4_STREAM_C
     }
     if (repacked) {
         if (bits == 4) return launch_stream_b<4, true>(p, sp, grid, stream);

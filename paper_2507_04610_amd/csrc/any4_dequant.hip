@@ -15,7 +15,7 @@ __global__ __launch_bounds__(256) void dequant_kernel(const uint32_t* __restrict
                                                       const uint16_t* __restrict__ lut,
                                                       const uint16_t* __restrict__ scale,
                                                       const uint16_t* __restrict__ offset,
-                                                      int64_t K, float* __restrict__ w) {
+                                                      int64_t K, int lr, float* __restrict__ w) {
     constexpr int L = 1 << BITS;
     constexpr uint32_t mask = L - 1;
     __shared__ float table[L];
@@ -24,7 +24,7 @@ __global__ __launch_bounds__(256) void dequant_kernel(const uint32_t* __restrict
     __syncthreads();
 
     const uint32_t* row = codes + n * row_words(K, BITS);
-    const int64_t G = K / kGroup;
+    const int64_t G = (K / kGroup) >> lr;               // scales per row: one per 128 << lr weights
     const int quads = (int)(K / 4);                     // 4 weights = 4*BITS code bits
     float4* out = reinterpret_cast<float4*>(w + n * K);
     for (int q = threadIdx.x; q < quads; q += 256) {
@@ -33,7 +33,7 @@ __global__ __launch_bounds__(256) void dequant_kernel(const uint32_t* __restrict
         uint64_t window = row[word];
         if (BITS == 3 && sh > 20) window |= (uint64_t)row[word + 1] << 32;   // 12 bits straddle
         const uint32_t c4 = (uint32_t)(window >> sh);
-        const int g = q >> 5;                           // (4q) / 128
+        const int g = (q >> 5) >> lr;                   // (4q) / group size
         const float s = bf16_to_f32(scale[n * G + g]);
         const float o = bf16_to_f32(offset[n * G + g]);
         float4 r;
@@ -46,14 +46,14 @@ __global__ __launch_bounds__(256) void dequant_kernel(const uint32_t* __restrict
 }
 
 hipError_t launch_dequant(const uint32_t* codes, const uint16_t* lut, const uint16_t* scale,
-                          const uint16_t* offset, int64_t N, int64_t K, int bits,
+                          const uint16_t* offset, int64_t N, int64_t K, int bits, int lr,
                           float* w, hipStream_t stream) {
     if (N > 0x7FFFFFFF || K > (int64_t)1 << 28) return hipErrorInvalidValue;
     const dim3 grid((unsigned)N), block(256);
     switch (bits) {
-        case 4: hipLaunchKernelGGL(dequant_kernel<4>, grid, block, 0, stream, codes, lut, scale, offset, K, w); break;
-        case 3: hipLaunchKernelGGL(dequant_kernel<3>, grid, block, 0, stream, codes, lut, scale, offset, K, w); break;
-        default: hipLaunchKernelGGL(dequant_kernel<2>, grid, block, 0, stream, codes, lut, scale, offset, K, w); break;
+        case 4: hipLaunchKernelGGL(dequant_kernel<4>, grid, block, 0, stream, codes, lut, scale, offset, K, lr, w); break;
+        case 3: hipLaunchKernelGGL(dequant_kernel<3>, grid, block, 0, stream, codes, lut, scale, offset, K, lr, w); break;
+        default: hipLaunchKernelGGL(dequant_kernel<2>, grid, block, 0, stream, codes, lut, scale, offset, K, lr, w); break;
     }
     return hipGetLastError();
 }

@@ -86,7 +86,7 @@ __global__ __launch_bounds__(PTHREADS, 1) void prefill_kernel(
     const uint16_t* __restrict__ x, const uint32_t* __restrict__ codes,
     const uint16_t* __restrict__ lut, const uint16_t* __restrict__ scale,
     const uint16_t* __restrict__ offset, const uint16_t* __restrict__ xsums, int KP,
-    int64_t M, int64_t N, int64_t K, int repacked, int gm, int tail_first, int tail_s,
+    int64_t M, int64_t N, int64_t K, int lr, int repacked, int gm, int tail_first, int tail_s,
     unsigned long long* __restrict__ counters, float* __restrict__ partial, uint16_t* __restrict__ y) {
     constexpr int L = 1 << BITS;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -134,7 +134,7 @@ __global__ __launch_bounds__(PTHREADS, 1) void prefill_kernel(
     // the two output columns this lane owns (one per 32-wide n tile of its wavefront)
     const uint16_t* scol[2];
 #pragma unroll
-    for (int j = 0; j < 2; ++j) scol[j] = scale + min(n0 + wn * 64 + j * 32 + (lane & 31), N - 1) * G;
+    for (int j = 0; j < 2; ++j) scol[j] = scale + min(n0 + wn * 64 + j * 32 + (lane & 31), N - 1) * (G >> lr);   // group of 128 << lr weights
     // LDS byte addresses (the kernel has no static LDS: dynamic LDS starts at 0)
     const uint32_t tbase = kTableOff + (uint32_t)((wrow >> 3) * (32 << BITS) + (wrow & 7) * 4 + wq) * 4u;
     const uint32_t xwr = (uint32_t)(xr_row * PLD + xc8 * 8) * 2u;                         // + buf * kXBuf + p * 64 rows
@@ -326,7 +326,7 @@ __global__ __launch_bounds__(PTHREADS, 1) void prefill_kernel(
     //      codes of step s + 3.  The last step stages a repeat of step T - 1 into a buffer that is
     //      not read again.
     for (int g = g_lo; g < g_hi; ++g) {
-        const uint32_t sraw0 = scol[0][g], sraw1 = scol[1][g];
+        const uint32_t sraw0 = scol[0][g >> lr], sraw1 = scol[1][g >> lr];
         const int s = 2 * g;
         step(B0{}, Yes{}, No{}, q1, min(s + 3, T - 1), min(s + 2, T - 1), 0u, 0u);
         lds_barrier();
@@ -346,7 +346,7 @@ __global__ __launch_bounds__(PTHREADS, 1) void prefill_kernel(
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const int gg = (k0 + wq * 16 + 2 * j) >> 1;
-            const uint32_t b = gg >= g_lo && gg < g_hi ? offset[wn_glob * G + gg] : 0u;
+            const uint32_t b = gg >= g_lo && gg < g_hi ? offset[wn_glob * (G >> lr) + (gg >> lr)] : 0u;
             pk[j] = b | (b << 16);
         }
 #pragma unroll
@@ -457,7 +457,7 @@ size_t prefill_workspace_bytes(int64_t M, int64_t N, int64_t K, int cus) {
 
 hipError_t launch_prefill(const uint16_t* x, const uint32_t* codes, const uint16_t* lut,
                           const uint16_t* scale, const uint16_t* offset,
-                          int64_t M, int64_t N, int64_t K, int bits, bool repacked, int cus,
+                          int64_t M, int64_t N, int64_t K, int bits, int lr, bool repacked, int cus,
                           uint16_t* y, void* workspace, hipStream_t stream) {
     const PrefillPlan pp = plan_prefill(M, N, K, cus);
     const int64_t units = M * (K / kGroup);
@@ -479,7 +479,7 @@ hipError_t launch_prefill(const uint16_t* x, const uint32_t* codes, const uint16
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)prefill_lds_bytes(B));           \
         if (e != hipSuccess) return e;                                                                            \
         hipLaunchKernelGGL(prefill_kernel<B>, grid, block, prefill_lds_bytes(B), stream, x, codes, lut, scale,    \
-                           offset, xsums, KP, M, N, K, repacked ? 1 : 0, gm, tail_first, tail_s, counters, partial, y); \
+                           offset, xsums, KP, M, N, K, lr, repacked ? 1 : 0, gm, tail_first, tail_s, counters, partial, y); \
     } while (0)
     switch (bits) {
         case 4: ANY4_PREFILL(4); break;

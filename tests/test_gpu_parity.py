@@ -274,6 +274,58 @@ def test_gemm_few_dozen_rows(any4, oracle, bits, M, N, K):
     run_gemm_case(any4, oracle, M, N, K, bits, seed=inputs.case_seed(6, bits, M))
 
 
+# ------------------------------------------------------------------------------ other group sizes
+def coarse(cs, group):
+    """one scale / offset per `group` weights, taken from the generated 128-wide ones"""
+    r = group // 128
+    return np.ascontiguousarray(cs.scale[:, ::r]), np.ascontiguousarray(cs.offset[:, ::r])
+
+
+@pytest.mark.parametrize("bits", (4, 3, 2))
+@pytest.mark.parametrize("group", (256, 512, 1024))
+@pytest.mark.parametrize("N,K", [(5, 1024), (130, 2048), (17, 14336)])
+def test_dequant_grouped_bit_exact(any4, oracle, bits, group, N, K):
+    if K % group:
+        pytest.skip("the group must divide K")
+    cs = inputs.make_case(1, N, K, bits, seed=inputs.case_seed(7, bits, group))
+    sc, of = coarse(cs, group)
+    packed = oracle.pack(cs.codes_u8, bits)
+    w_ref = oracle.dequant(packed, cs.lut, sc, of, K, bits, group=group)
+    w = any4.any4_dequant(dev_codes(packed), dev_bf16(cs.lut), dev_bf16(sc), dev_bf16(of), K, bits, group=group)
+    torch.cuda.synchronize()
+    assert np.array_equal(w.cpu().numpy().view(np.uint32), w_ref.view(np.uint32))
+
+
+@pytest.mark.parametrize("bits", (4, 3, 2))
+@pytest.mark.parametrize("group", (256, 512, 1024))
+@pytest.mark.parametrize("M,N,K", [(1, 40, 1024), (5, 333, 4096), (16, 100, 2048), (2, 64, 14336), (1, 2049, 1024),
+                                   (32, 256, 4096), (100, 200, 1024), (300, 130, 2048)])
+def test_gemm_grouped(any4, oracle, bits, group, M, N, K):
+    """Small M (streaming kernel, every wavefront reads the scales of its own chunks), a few dozen
+    rows (the same kernel, 16 rows per launch) and large M (matrix cores, K slices included)."""
+    if K % group:
+        pytest.skip("the group must divide K")
+    cs = inputs.make_case(M, N, K, bits, seed=inputs.case_seed(8, bits, group + M))
+    sc, of = coarse(cs, group)
+    packed = oracle.pack(cs.codes_u8, bits)
+    y64 = oracle.gemm(cs.x, packed, cs.lut, sc, of, K, bits, threads=8, group=group)
+    y = any4.any4_gemm(dev_bf16(cs.x), dev_codes(packed), dev_bf16(cs.lut), dev_bf16(sc), dev_bf16(of), bits, group=group)
+    torch.cuda.synchronize()
+    check_gemm(y, y64, oracle.rms(y64), ("group", group, M, N, K, bits))
+
+
+def test_grouped_rejects_other_group_sizes(any4):
+    cs = inputs.make_case(1, 16, 1024, 4, 3)
+    codes = any4.any4_pack(torch.from_numpy(cs.codes_u8).cuda(), 4)
+    for bad in (64, 192, 2048, 0, -128):
+        with pytest.raises(any4.Any4Error):
+            any4.any4_gemm(dev_bf16(cs.x), codes, dev_bf16(cs.lut), dev_bf16(cs.scale), dev_bf16(cs.offset), 4, group=bad)
+    cs = inputs.make_case(1, 16, 640, 4, 3)                 # 640 is not a multiple of 256
+    codes = any4.any4_pack(torch.from_numpy(cs.codes_u8).cuda(), 4)
+    with pytest.raises(any4.Any4Error):
+        any4.any4_dequant(codes, dev_bf16(cs.lut), dev_bf16(cs.scale), dev_bf16(cs.offset), 640, 4, group=256)
+
+
 # ------------------------------------------------------------------------------ tile-major re-layout
 @pytest.mark.parametrize("bits", (4, 3, 2))
 @pytest.mark.parametrize("N,K", [(16, 128), (21, 256), (1, 128), (257, 1152), (64, 4096), (5, 14336)])
