@@ -32,7 +32,8 @@
  * table, unit-vector activations), reduction to a library fp64 matmul, pack /
  * unpack round trips, and the bits-per-weight figure printed in section 2.4.1.
  * Group sizes other than 128 (the *_g functions): expanding the scales to one per 128 weights
- * must give the 128-group result bit for bit, a single group per row has a closed form.
+ * (or, for groups of 64, to one per 64) must give the finer-group result bit for bit, a single
+ * group per row has a closed form, groups of 64 are checked block by block against numpy.
  * The tile-major re-layout (any4o_repack) is pinned by a word-level transpose written
  * with numpy, by reading single codes back out of it, by its zero padding and by the
  * multiset of its words.
@@ -127,11 +128,11 @@ int any4o_repack(const uint32_t *packed, int64_t N, int64_t K, int bits, uint32_
  * differs in bit pattern from the fused result (expected 0: a product of two bf16
  * numbers is exact in fp32), or -1 on bad arguments. */
 static int group_ok(int64_t K, int64_t group) {
-    return group >= ANY4O_GROUP && group % ANY4O_GROUP == 0 && K % group == 0;
+    return group >= 64 && group % 64 == 0 && K % group == 0;
 }
 
-/* the same with a group of `group` weights (a multiple of 128 that divides K; the paper's
- * Table 4 varies the group size): scale / offset are [N][K / group] */
+/* the same with a group of `group` weights (a multiple of 64 that divides K; the paper's
+ * Table 4 varies the group size from 64 to 1024): scale / offset are [N][K / group] */
 int64_t any4o_dequant_g(const uint32_t *packed, const uint16_t *lut, const uint16_t *scale,
                         const uint16_t *offset, int64_t N, int64_t K, int bits, int64_t group, float *w) {
     if (!packed || !lut || !scale || !offset || !w || N < 1 || K < 1 || K % ANY4O_GROUP || !bits_ok(bits) ||

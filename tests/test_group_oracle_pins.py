@@ -52,10 +52,60 @@ def test_one_group_per_row_has_a_closed_form(oracle):
     assert np.abs(other - want).max() > 1e-3 * np.abs(want).max()
 
 
-def test_group_must_divide_k_and_be_a_multiple_of_128(oracle):
+def fine_case(N, K, bits, seed):
+    """scales / offsets per 64 weights: two independent draws interleaved along K"""
+    a, b = inputs.make_case(3, N, K, bits, seed), inputs.make_case(3, N, K, bits, seed + 1000)
+    sc = np.ascontiguousarray(np.stack([a.scale, b.scale], axis=2).reshape(N, -1))
+    of = np.ascontiguousarray(np.stack([a.offset, b.offset], axis=2).reshape(N, -1))
+    return a, sc, of
+
+
+@pytest.mark.parametrize("bits", (4, 3, 2))
+def test_groups_of_128_equal_groups_of_64_with_every_scale_twice(oracle, bits):
+    N, K = 6, 1024
+    cs = inputs.make_case(3, N, K, bits, 11)
+    packed = oracle.pack(cs.codes_u8, bits)
+    sc64, of64 = np.repeat(cs.scale, 2, axis=1), np.repeat(cs.offset, 2, axis=1)
+    w_64 = oracle.dequant(packed, cs.lut, sc64, of64, K, bits, group=64)
+    w_128 = oracle.dequant(packed, cs.lut, cs.scale, cs.offset, K, bits)
+    assert np.array_equal(w_64.view(np.uint32), w_128.view(np.uint32))
+    assert np.array_equal(oracle.gemm(cs.x, packed, cs.lut, sc64, of64, K, bits, group=64),
+                          oracle.gemm(cs.x, packed, cs.lut, cs.scale, cs.offset, K, bits))
+
+
+@pytest.mark.parametrize("bits", (4, 3, 2))
+def test_groups_of_64_block_by_block(oracle, bits):
+    """y = sum over blocks of 64 columns of s_b * (x_b . LUT[codes_b]) + o_b * sum(x_b), written with
+    numpy in fp64; the oracle rounds every weight to fp32 first, hence the 2^-23 allowance.  The
+    two halves of a 128-chunk carry unrelated scales, so a mix-up of halves cannot pass."""
+    N, K = 5, 512
+    cs, sc, of = fine_case(N, K, bits, 21)
+    packed = oracle.pack(cs.codes_u8, bits)
+    y = oracle.gemm(cs.x, packed, cs.lut, sc, of, K, bits, group=64)
+    w = oracle.dequant(packed, cs.lut, sc, of, K, bits, group=64)
+    lut = inputs.bf16_bits_to_f32(cs.lut).astype(np.float64)
+    x = inputs.bf16_bits_to_f32(cs.x).astype(np.float64)
+    v = np.take_along_axis(lut, cs.codes_u8.astype(np.int64), axis=1)            # [N, K]
+    s, o = inputs.bf16_bits_to_f32(sc).astype(np.float64), inputs.bf16_bits_to_f32(of).astype(np.float64)
+    want = np.zeros_like(y)
+    terms = np.zeros_like(y)
+    for b in range(K // 64):
+        xb, vb = x[:, 64 * b:64 * b + 64], v[:, 64 * b:64 * b + 64]
+        want += (xb @ vb.T) * s[None, :, b] + xb.sum(axis=1)[:, None] * o[None, :, b]
+        terms += (np.abs(xb) @ np.abs(vb).T) * np.abs(s)[None, :, b] + np.abs(xb).sum(axis=1)[:, None] * np.abs(o)[None, :, b]
+        # single weights of the block: one element each, straight from the definition
+        for n in (0, N - 1):
+            k = 64 * b + (7 * b + n) % 64
+            assert w[n, k] == np.float32(v[n, k] * s[n, b] + o[n, b])
+    assert np.all(np.abs(y - want) <= 2.0 ** -23 * terms)
+    swapped = oracle.gemm(cs.x, packed, cs.lut, sc.reshape(N, -1, 2)[:, :, ::-1].reshape(N, -1).copy(), of, K, bits, group=64)
+    assert np.abs(swapped - want).max() > 1e-3 * np.abs(want).max()
+
+
+def test_group_must_divide_k_and_be_a_multiple_of_64(oracle):
     cs, sc, of = case(4, 1024, 4, 256, 1)
     packed = oracle.pack(cs.codes_u8, 4)
-    for bad in (64, 192, 768, 2048):
+    for bad in (32, 96, 192, 768, 2048):
         with pytest.raises(ValueError):
             oracle.dequant(packed, cs.lut, sc, of, 1024, 4, group=bad)
     with pytest.raises(ValueError):
