@@ -105,9 +105,9 @@ size_t any4_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int bits);
  * any4_dequant_grouped / any4_gemm_grouped - the same two operations with a scale and an offset
  * shared by `group` consecutive weights along K instead of 128 (section 2.5.1, "Groupwise"; the
  * paper's Table 4 varies the group size): scale and offset are bf16 [N][K/group].
- *   group   128, 256, 512 or 1024, and a divisor of K; anything else returns ANY4_ERR_SHAPE
- *           (a group of 64 is not supported: the small-M kernel's matrix instruction sums over
- *           128 weights at a time).
+ *   group   64, 128, 256, 512 or 1024 (the range of Table 4), and a divisor of K; anything else
+ *           returns ANY4_ERR_SHAPE.  With group = 64 and M <= 16 the weights are streamed once per
+ *           8 rows of x (two launches for M > 8); for 16 < M the matrix-core kernel is used.
  * Every other argument, the workspace size (any4_gemm_workspace_bytes) and the error behaviour
  * are those of any4_dequant / any4_gemm; with group = 128 the calls are identical to them.
  * any4_gemm_grouped needs a table (lut != NULL) unless group = 128.

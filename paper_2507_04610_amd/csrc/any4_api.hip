@@ -14,16 +14,17 @@ static int shape_check(int64_t N, int64_t K, int bits) {
     return ANY4_OK;
 }
 
-// log2(group / 128) for the group sizes the kernels take (a multiple of 128 that divides K), else -1
-static int group_shift(int64_t K, int group) {
-    for (int lr = 0; lr <= 3; ++lr)
-        if (group == (ANY4_GROUP << lr)) return K % group == 0 ? lr : -1;
-    return -1;
+// log2(group / 128) for the group sizes the kernels take (64 .. 1024, a divisor of K): -1 .. 3
+static bool group_shift(int64_t K, int group, int* lr) {
+    for (int l = -1; l <= 3; ++l)
+        if (group == (l < 0 ? ANY4_GROUP / 2 : ANY4_GROUP << l)) { *lr = l; return K % group == 0; }
+    return false;
 }
 
 constexpr int kDecodeMaxM = 16;
 constexpr int kStreamMaxM = 16;
 constexpr int kChunkedMaxM = 128;      // above this the matrix-core kernel is always taken
+constexpr int kFineRows = 8;           // groups of 64 weights: rows of x per launch of the streaming kernel
 
 // Compute units of the current device (256 on MI355X); only shapes the work split, never results.
 int device_compute_units() {
@@ -78,6 +79,9 @@ GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int bits) {
                 p.sp_tail = tail;
                 p.ksplit = full.slabs;
                 p.workspace = full.workspace > tail.workspace ? full.workspace : tail.workspace;
+                // (groups of 64 weights go to the matrix-core kernel for these M: room for either)
+                const size_t wm = prefill_workspace_bytes(M, N, K, cus);
+                if (wm > p.workspace) p.workspace = wm;
                 return p;
             }
         }
@@ -120,8 +124,8 @@ int any4_dequant_grouped(const uint32_t* codes, const uint16_t* lut, const uint1
     if (!codes || !scale || !offset || !w) return ANY4_ERR_NULL;
     if (!lut && bits != 4) return ANY4_ERR_NULL;           // no table = the 4-bit integer grid only
     if (int rc = shape_check(N, K, bits)) return rc;
-    const int lr = group_shift(K, group);
-    if (lr < 0) return ANY4_ERR_SHAPE;
+    int lr;
+    if (!group_shift(K, group, &lr)) return ANY4_ERR_SHAPE;
     if (!aligned16(codes) || !aligned16(lut) || !aligned16(scale) || !aligned16(offset) || !aligned16(w))
         return ANY4_ERR_ALIGN;
     return launch_dequant(codes, lut, scale, offset, N, K, bits, lr, w, static_cast<hipStream_t>(stream)) == hipSuccess
@@ -169,19 +173,29 @@ static int gemm_any_layout(const uint16_t* x, const uint32_t* codes, bool repack
     if (!lut && (bits != 4 || repacked)) return ANY4_ERR_NULL;       // no table = the 4-bit integer grid, plain layout only
     if (int rc = shape_check(N, K, bits)) return rc;
     if (M < 1) return ANY4_ERR_SHAPE;
-    const int lr = group_shift(K, group);
-    if (lr < 0) return ANY4_ERR_SHAPE;
-    if (!lut && lr > 0) return ANY4_ERR_NULL;                            // the table-free path has groups of 128
+    int lr;
+    if (!group_shift(K, group, &lr)) return ANY4_ERR_SHAPE;
+    if (!lut && lr != 0) return ANY4_ERR_NULL;                           // the table-free path has groups of 128
     if (!aligned16(x) || !aligned16(codes) || !aligned16(lut) || !aligned16(scale) ||
         !aligned16(offset) || !aligned16(y) || !aligned16(workspace))
         return ANY4_ERR_ALIGN;
     const GemmPlan plan = plan_gemm(M, N, K, bits);
     // K beyond the streaming kernel's range: only the plain layout with groups of 128
-    if ((repacked || lr > 0) && plan.decode && !plan.stream) return ANY4_ERR_SHAPE;
+    if ((repacked || lr != 0) && plan.decode && !plan.stream) return ANY4_ERR_SHAPE;
     if (plan.workspace > 0 && (!workspace || workspace_bytes < plan.workspace)) return ANY4_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t e;
-    if (plan.chunked) {
+    if (lr < 0 && plan.stream && !plan.chunked) {
+        // groups of 64 weights, M <= 16: the streaming kernel takes 8 rows of x a launch
+        e = hipSuccess;
+        for (int64_t m0 = 0; m0 < M && e == hipSuccess; m0 += kFineRows) {
+            const int64_t rows = M - m0 < kFineRows ? M - m0 : kFineRows;
+            e = launch_decode_stream(x + m0 * K, codes, lut, scale, offset, rows, N, K, bits, lr, false, plan.sp,
+                                     y + m0 * N, workspace, s);
+        }
+    } else if (lr < 0) {
+        e = launch_prefill(x, codes, lut, scale, offset, M, N, K, bits, lr, false, device_compute_units(), y, workspace, s);
+    } else if (plan.chunked) {
         // launches run one after the other on the stream and leave the workspace's counters clean
         e = hipSuccess;
         for (int64_t m0 = 0; m0 < M && e == hipSuccess; m0 += kStreamMaxM) {

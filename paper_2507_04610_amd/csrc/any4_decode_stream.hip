@@ -83,13 +83,15 @@ constexpr int kWaves = 8;                              // wavefronts per block: 
 constexpr int table_bytes(int bits) { return bits == 4 ? 256 * 256 : (bits == 3 ? 64 * 256 : 2 * 256 * 256); }
 constexpr int kListTiles = 1024;                       // tiles whose slabs a block combines per round
 constexpr int kAuxDist = 4;                            // tiles between the load of a tile's small inputs and their use
-constexpr int kAuxRow = 72;                            // LDS bytes per row of scales (64 + 8 of padding against bank conflicts)
-constexpr int kAuxScale = 0, kAuxOffset = kTile * kAuxRow, kAuxLut = 2 * kTile * kAuxRow;
-constexpr int kAuxSlot = kAuxLut + kTile * 32;         // 2816 B: scales, offsets and tables of one tile
+// LDS bytes per row of scales: 32 entries + 8 bytes of padding against bank conflicts; with groups of
+// 64 weights (`fine`) 64 entries + 16 bytes
+constexpr int aux_row(bool fine) { return fine ? 144 : 72; }
+constexpr int aux_lut(bool fine) { return 2 * kTile * aux_row(fine); }
+constexpr int aux_slot(bool fine) { return aux_lut(fine) + kTile * 32; }    // 2816 B (5120 B): scales, offsets and tables of one tile
 constexpr int kRedBytes = 2 * kWaves * 4 * 64 * 4;     // [2][kWaves][4][64] fp32 partial sums
 constexpr int aux_base(int bits) { return table_bytes(bits) + kRedBytes; }
-constexpr int list_base(int bits) { return aux_base(bits) + kAuxDist * kAuxSlot; }
-constexpr int lds_bytes(int bits) { return list_base(bits) + (1 + kListTiles) * 4; }
+constexpr int list_base(int bits, bool fine) { return aux_base(bits) + kAuxDist * aux_slot(fine); }
+constexpr int lds_bytes(int bits, bool fine = false) { return list_base(bits, fine) + (1 + kListTiles) * 4; }
 
 #ifdef ANY4_STAMPS
 // timing probes for tuning builds: time stamps at the natural LDS synchronisation points of a tile
@@ -144,9 +146,24 @@ __device__ __forceinline__ float sum8(const uint4& v) {
 //         A code c becomes the bf16 number 128 + c by OR-ing it into the mantissa of 128.0
 //         (0x4300 | c), and the surplus 136 * scale * (group sum of x) is taken off again by two more
 //         exact bf16 terms (-128 * scale and -8 * scale) that ride in the offset MFMA.
-template <int BITS, int GW, bool AUX, bool NOLUT, bool REPACK, bool COARSE>
+// COARSE  groups of 256, 512 or 1024 weights: chunk g of 128 weights reads scale / offset g >> lr
+// FINE    groups of 64 weights, M <= 8.  The codes, lookups and B operands are those of a chunk of 128;
+//         the two halves of a chunk are told apart on the activation side.  Operand row r of the
+//         matrix instructions holds activation row r % 8 with the quarters of the other half
+//         zeroed (r < 8: quarters 0, 1 = the chunk's first 64 weights; r >= 8: quarters 2, 3), so
+//         output rows m and m + 8 are the two halves' partial sums of activation row m.  An
+//         accumulator lane holds rows 4q .. 4q + 3: lanes with q < 2 take the scale of the first
+//         half, the others that of the second.  In the offset MFMA the group sums of the first
+//         halves sit in the k-slots of quarter 0 (rows < 8) and those of the second halves in the
+//         slots of quarter 1 (rows >= 8), facing the two offsets.  Rows m and m + 8 are added
+//         when the wavefronts' partial sums are.
+template <int BITS, int GW, bool AUX, bool NOLUT, bool REPACK, bool COARSE, bool FINE>
 __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Params p) {
     static_assert(!COARSE || (!NOLUT && !REPACK), "groups above 128 weights: table-based, plain layout");
+    static_assert(!FINE || (!COARSE && !NOLUT && !REPACK), "groups of 64 weights: table-based, plain layout");
+    static_assert(!(FINE && AUX && BITS == 2), "the larger slots of the shared small inputs do not fit beside the any2 tables");
+    constexpr int kAuxRow = aux_row(FINE && AUX), kAuxScale = 0, kAuxOffset = kTile * kAuxRow, kAuxLut = aux_lut(FINE && AUX);
+    constexpr int kAuxSlot = aux_slot(FINE && AUX);
     static_assert(!NOLUT || BITS == 4, "the table-free path is the 4-bit integer grid");
     static_assert(!(NOLUT && REPACK), "the table-free path reads the plain layout only");
     static_assert(BITS == 4 || BITS == 3 || BITS == 2, "code width");
@@ -159,10 +176,10 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     float* red = reinterpret_cast<float*>(smem + table_bytes(BITS));    // [2][WAVES][4][64]
     unsigned char* const aux = smem + aux_base(BITS);                   // [kAuxDist] slots
-    int* lastlist = reinterpret_cast<int*>(smem + list_base(BITS));     // [0] = count
+    int* lastlist = reinterpret_cast<int*>(smem + list_base(BITS, FINE && AUX));     // [0] = count
 #ifdef ANY4_STAMPS
     const long long stamp_entry = wall_clock64();
-    long long* stamps = reinterpret_cast<long long*>(smem + lds_bytes(BITS));
+    long long* stamps = reinterpret_cast<long long*>(smem + lds_bytes(BITS, FINE && AUX));
     for (int i = threadIdx.x; i < WAVES * kStampSteps * 4; i += WAVES * 64) stamps[i] = 0;
     __syncthreads();
 #define ST_MARK(i) do { if ((threadIdx.x & 63) == 0) stamps[(((threadIdx.x >> 6) * kStampSteps) + kStampSteps - 1) * 4 + (i)] = wall_clock64(); } while (0)
@@ -200,7 +217,7 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
     const uint32_t row_bytes = (uint32_t)(K * BITS / 8);
     const uint32_t vc_norm = (uint32_t)n * row_bytes + (uint32_t)q * QB, vc_last = (uint32_t)nc * row_bytes + (uint32_t)q * QB;
     const uint32_t vl_norm = (uint32_t)n * LUTB, vl_last = (uint32_t)nc * LUTB;
-    const int lr = COARSE ? p.lr : 0, GS = G >> lr;      // scales / offsets per row
+    const int lr = COARSE ? p.lr : 0, GS = FINE ? 2 * G : G >> lr;      // scales / offsets per row
     const uint32_t vs_norm = (uint32_t)n * (uint32_t)GS * 2u, vs_last = (uint32_t)nc * (uint32_t)GS * 2u;
     const char* const codes_b = reinterpret_cast<const char*>(p.codes);
     const char* const lut_b = reinterpret_cast<const char*>(p.lut);
@@ -305,9 +322,20 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
     //      row's table by lanes j < 2 (any4, 16 bytes each) or j = 0 (any3: 16 bytes, any2: 8)) and
     //      written to an LDS slot two tiles later.  Table rows keep a 32-byte stride in the slot.
     uint2 axs[2], axo[2];
+    uint4 fxs[2], fxo[2];                                  // FINE: twice the entries
     uint4 axl;
     auto aux_load = [&](int t) {
-        if constexpr (!COARSE) {
+        if constexpr (FINE) {
+            // two entries per chunk of 128: lane (n, j) loads those of chunks 4j .. 4j+3 and 16 + 4j .. + 3
+            const int64_t tile_off = (int64_t)t * (kTile * 2) * GS + gs0 * 4;
+            const uint32_t vs = t == last_tile ? vs_last : vs_norm;
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                const uint32_t go = (uint32_t)min((c * 4 + q) * 4, max(sg, 4) - 4) * 4u;
+                fxs[c] = *reinterpret_cast<const uint4*>(scale_b + tile_off + vs + go);
+                fxo[c] = *reinterpret_cast<const uint4*>(offset_b + tile_off + vs + go);
+            }
+        } else if constexpr (!COARSE) {
             // lanes past the slab's groups repeat its last four: the loads are unconditional
             const int64_t tile_off = (int64_t)t * (kTile * 2) * G + gs0 * 2;
             const uint32_t vs = t == last_tile ? vs_last : vs_norm;
@@ -347,6 +375,11 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
 #pragma unroll
         for (int c = 0; c < 2; ++c)
             if ((c * 4 + q) * 4 < sg) {
+                if constexpr (FINE) {
+                    *reinterpret_cast<uint4*>(s + kAuxScale + n * kAuxRow + (c * 4 + q) * 16) = fxs[c];
+                    *reinterpret_cast<uint4*>(s + kAuxOffset + n * kAuxRow + (c * 4 + q) * 16) = fxo[c];
+                    continue;
+                }
                 uint2 sv = axs[c], ov = axo[c];
                 if constexpr (COARSE) {
                     sv = make_uint2(sv.x | (sv.x << 16), sv.y | (sv.y << 16));
@@ -367,8 +400,25 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
     // ---- scales and offsets of the wavefront's groups for one tile, as packed bf16 pairs
     //      (group gi in half gi % 2 of word gi / 2)
     auto aux_read_so = [&](uint32_t (&sp)[NP], uint32_t (&op)[NP], int slot) {
-        const unsigned char* s = aux + slot * kAuxSlot + n * kAuxRow + (w * GW) * 2;
-        if constexpr (GW == 4) {
+        const unsigned char* s = aux + slot * kAuxSlot + n * kAuxRow + (w * GW) * (FINE ? 4 : 2);
+        if constexpr (FINE) {
+            // a chunk's two entries are one word (first half | second half << 16); an accumulator lane
+            // takes the scale of half q / 2, an offset-operand lane the offset of half q % 2
+            const uint32_t ssel = (q >> 1) ? 0x07060302u : 0x05040100u, osel = (q & 1) ? 0x07060302u : 0x05040100u;
+            if constexpr (GW == 4) {
+                const uint4 a = *reinterpret_cast<const uint4*>(s + kAuxScale), b = *reinterpret_cast<const uint4*>(s + kAuxOffset);
+                sp[0] = __builtin_amdgcn_perm(a.y, a.x, ssel); sp[1] = __builtin_amdgcn_perm(a.w, a.z, ssel);
+                op[0] = __builtin_amdgcn_perm(b.y, b.x, osel); op[1] = __builtin_amdgcn_perm(b.w, b.z, osel);
+            } else if constexpr (GW == 2) {
+                const uint2 a = *reinterpret_cast<const uint2*>(s + kAuxScale), b = *reinterpret_cast<const uint2*>(s + kAuxOffset);
+                sp[0] = __builtin_amdgcn_perm(a.y, a.x, ssel);
+                op[0] = __builtin_amdgcn_perm(b.y, b.x, osel);
+            } else {
+                const uint32_t a = *reinterpret_cast<const uint32_t*>(s + kAuxScale), b = *reinterpret_cast<const uint32_t*>(s + kAuxOffset);
+                sp[0] = __builtin_amdgcn_perm(0u, a, ssel) & 0xFFFFu;
+                op[0] = __builtin_amdgcn_perm(0u, b, osel) & 0xFFFFu;
+            }
+        } else if constexpr (GW == 4) {
             const uint2 a = *reinterpret_cast<const uint2*>(s + kAuxScale), b = *reinterpret_cast<const uint2*>(s + kAuxOffset);
             sp[0] = a.x; sp[1] = a.y; op[0] = b.x; op[1] = b.y;
         } else if constexpr (GW == 2) {
@@ -392,8 +442,12 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
         const uint32_t v = t == last_tile ? vs_last : vs_norm;
 #pragma unroll
         for (int gi = 0; gi < GW; ++gi) {
-            sr[gi] = *reinterpret_cast<const uint16_t*>(scale_b + tile_off + (group_of(gi) >> lr) * 2 + v);
-            orw[gi] = *reinterpret_cast<const uint16_t*>(offset_b + tile_off + (group_of(gi) >> lr) * 2 + v);
+            // FINE: accumulator lanes of quarters 0, 1 / 2, 3 scale the first / second half of the chunk;
+            // offset-operand lanes of quarter 0 / 1 carry the first / second half's offset
+            const uint32_t si = FINE ? (uint32_t)(2 * group_of(gi)) + (uint32_t)(q >> 1) : (uint32_t)(group_of(gi) >> lr);
+            const uint32_t oi = FINE ? (uint32_t)(2 * group_of(gi)) + (uint32_t)(q & 1) : (uint32_t)(group_of(gi) >> lr);
+            sr[gi] = *reinterpret_cast<const uint16_t*>(scale_b + tile_off + si * 2u + v);
+            orw[gi] = *reinterpret_cast<const uint16_t*>(offset_b + tile_off + oi * 2u + v);
         }
     };
     auto pack_so = [&](uint32_t (&sp)[NP], uint32_t (&op)[NP], const uint32_t (&sr)[GW], const uint32_t (&orw)[GW]) {
@@ -496,11 +550,14 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
             for (int m = 0; m < ROWS; ++m)
                 if (lane < GW * 16 && r0 + m < M) stage[m * (GW * 16) + lane] = xraw[r0 + m];
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-            if (n >= r0 && n < min(M, r0 + ROWS)) {
+            // FINE: operand row n is activation row n % 8, restricted to the quarters of half n / 8
+            const int xrow = FINE ? (n & 7) : n;
+            const bool mine = FINE ? (n >> 3) == (q >> 1) : true;
+            if (mine && xrow >= r0 && xrow < min(M, r0 + ROWS)) {
 #pragma unroll
                 for (int gi = 0; gi < GW; ++gi)
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) xa[gi][j] = stage[(n - r0) * (GW * 16) + gi * 16 + q * 4 + j];
+                    for (int j = 0; j < 4; ++j) xa[gi][j] = stage[(xrow - r0) * (GW * 16) + gi * 16 + q * 4 + j];
             }
         };
         if (compact) {
@@ -540,7 +597,7 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
             lo[gi] = f32_to_bf16(sgi - bf16_to_f32(hi[gi]));
         }
         xo = make_uint4(hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16), lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16));
-        if (NOLUT ? q > 2 : q > 0) xo = make_uint4(0, 0, 0, 0);
+        if (FINE ? q != (n >> 3) : (NOLUT ? q > 2 : q > 0)) xo = make_uint4(0, 0, 0, 0);
     }
     if constexpr (NOLUT) {
         // operand order of the table-free path: elements (0, 4), (1, 5), (2, 6), (3, 7) of every 8
@@ -631,6 +688,12 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
             float s = 0.f;
 #pragma unroll
             for (int ww = 0; ww < WAVES; ++ww) s += src[ww * 4 * 64];
+            if constexpr (FINE) {                          // the second halves of the chunks: output row m + 8
+                float s2 = 0.f;
+#pragma unroll
+                for (int ww = 0; ww < WAVES; ++ww) s2 += src[ww * 4 * 64 + 32];
+                s += s2;
+            }
             const int64_t col = (int64_t)t * kTile + nn;
             if (col < N) {
                 if (p.slabs == 1) p.y[(int64_t)m * N + col] = (uint16_t)f32_to_bf16(s);
@@ -875,13 +938,13 @@ StreamPlan plan_stream(int64_t M, int64_t N, int64_t K, int cus) {
     return best;
 }
 
-template <int BITS, int GW, bool AUX, bool NOLUT = false, bool REPACK = false, bool COARSE = false>
+template <int BITS, int GW, bool AUX, bool NOLUT = false, bool REPACK = false, bool COARSE = false, bool FINE = false>
 static hipError_t launch_stream_t(const Params& p, int grid, hipStream_t stream) {
-    auto kern = stream::decode_stream_kernel<BITS, GW, AUX, NOLUT, REPACK, COARSE>;
+    auto kern = stream::decode_stream_kernel<BITS, GW, AUX, NOLUT, REPACK, COARSE, FINE>;
 #ifdef ANY4_STAMPS
-    constexpr int lds = stream::lds_bytes(BITS) + stream::kWaves * stream::kStampSteps * 4 * 8;
+    constexpr int lds = stream::lds_bytes(BITS, FINE && AUX) + stream::kWaves * stream::kStampSteps * 4 * 8;
 #else
-    constexpr int lds = stream::lds_bytes(BITS);
+    constexpr int lds = stream::lds_bytes(BITS, FINE && AUX);
 #endif
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds);
@@ -921,7 +984,7 @@ hipError_t launch_decode_stream(const uint16_t* x, const uint32_t* codes, const 
 #endif
     const int grid = sp.slabs * sp.blocks_per_slab;
     if (bits == 4 && lut == nullptr) {                     // the integer grid: no table
-        if (repacked || lr > 0) return hipErrorInvalidValue;
+        if (repacked || lr != 0) return hipErrorInvalidValue;
 #define ANY4_STREAM_NL(GW)                                                                 \
     (sp.aux ? launch_stream_t<4, GW, true, true>(p, grid, stream) : launch_stream_t<4, GW, false, true>(p, grid, stream))
         switch (sp.gw) {
@@ -930,6 +993,25 @@ hipError_t launch_decode_stream(const uint16_t* x, const uint32_t* codes, const 
             default: return ANY4_STREAM_NL(1);
         }
 #undef ANY4_STREAM_NL
+    }
+    if (lr < 0) {
+        // groups of 64 weights: at most 8 rows a launch
+        if (repacked || lr != -1 || M > stream::kTile / 2) return hipErrorInvalidValue;
+        // (any2: every wavefront reads its own scales - no room for the shared slots beside its tables)
+#define ANY4_STREAM_F(B, GW, SHARE)                                                        \
+        return sp.aux && SHARE ? launch_stream_t<B, GW, SHARE, false, false, false, true>(p, grid, stream)   \
+                               : launch_stream_t<B, GW, false, false, false, false, true>(p, grid, stream)
+#define ANY4_STREAM_FB(B, SHARE)                                                           \
+        switch (sp.gw) {                                                                   \
+            case 4: ANY4_STREAM_F(B, 4, SHARE);                                            \
+            case 2: ANY4_STREAM_F(B, 2, SHARE);                                            \
+            default: ANY4_STREAM_F(B, 1, SHARE);                                           \
+        }
+        if (bits == 4) { ANY4_STREAM_FB(4, true) }
+        if (bits == 3) { ANY4_STREAM_FB(3, true) }
+        ANY4_STREAM_FB(2, false)
+#undef ANY4_STREAM_FB
+#undef ANY4_STREAM_F
     }
     if (lr > 0) {
         // groups of 256 weights and more: the variants that read one scale per group

@@ -24,7 +24,8 @@ __global__ __launch_bounds__(256) void dequant_kernel(const uint32_t* __restrict
     __syncthreads();
 
     const uint32_t* row = codes + n * row_words(K, BITS);
-    const int64_t G = (K / kGroup) >> lr;               // scales per row: one per 128 << lr weights
+    const int gsh = 5 + lr;                             // log2(group size / 4), lr = -1 (groups of 64) .. 3
+    const int64_t G = K >> (gsh + 2);                   // scales per row: one per 128 << lr weights
     const int quads = (int)(K / 4);                     // 4 weights = 4*BITS code bits
     float4* out = reinterpret_cast<float4*>(w + n * K);
     for (int q = threadIdx.x; q < quads; q += 256) {
@@ -33,7 +34,7 @@ __global__ __launch_bounds__(256) void dequant_kernel(const uint32_t* __restrict
         uint64_t window = row[word];
         if (BITS == 3 && sh > 20) window |= (uint64_t)row[word + 1] << 32;   // 12 bits straddle
         const uint32_t c4 = (uint32_t)(window >> sh);
-        const int g = (q >> 5) >> lr;                   // (4q) / group size
+        const int g = q >> gsh;                         // (4q) / group size
         const float s = bf16_to_f32(scale[n * G + g]);
         const float o = bf16_to_f32(offset[n * G + g]);
         float4 r;

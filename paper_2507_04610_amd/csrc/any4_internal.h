@@ -53,9 +53,9 @@ hipError_t launch_prefill(const uint16_t* x, const uint32_t* codes, const uint16
 // Tile-major re-layout of the packed codes (any4_repack).
 hipError_t launch_repack(const uint32_t* codes, int64_t N, int64_t K, int bits, uint32_t* out, hipStream_t stream);
 
-// Matrix-core path: padded length of the "group" dimension (two bf16 columns per group of 128,
-// rounded up to the MFMA K granularity of 16) and the scratch it needs for the group sums of x.
-inline int prefill_kp(int64_t K) { return (int)((2 * (K / 128) + 15) / 16 * 16); }
+// Matrix-core path: padded length of the "group" dimension (two bf16 columns per group of 128 - of
+// 64 with `fine` - rounded up to the MFMA K granularity of 16) and the scratch it needs for the group sums of x.
+inline int prefill_kp(int64_t K, bool fine) { return (int)((2 * (K / (fine ? 64 : 128)) + 15) / 16 * 16); }
 // its work split (tiles of 256 x 128 outputs; the tiles of a thin last round are cut along K) and scratch
 struct PrefillPlan {
     int64_t gm, tiles, tail_tiles;

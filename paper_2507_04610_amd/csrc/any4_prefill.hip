@@ -51,37 +51,43 @@ __device__ __forceinline__ void lds_barrier() {                 // outstanding g
 
 // X[m][g] = sum of the 128 activations of group g, in fp32, stored as two bf16 (high part,
 // remainder) at xs[m][2g], xs[m][2g+1]; columns 2G .. KP-1 are zero.  16 lanes per (m, g).
+// `fine`: groups of 64 activations, 8 lanes each.
 __global__ __launch_bounds__(256) void group_sums_kernel(const uint16_t* __restrict__ x, int64_t M,
-                                                         int64_t K, int KP, uint16_t* __restrict__ xs) {
-    const int64_t G = K / kGroup;
-    const int64_t unit = ((int64_t)blockIdx.x * 256 + threadIdx.x) >> 4;     // (m, g), g fastest
-    const int sub = threadIdx.x & 15;
+                                                         int64_t K, int KP, int fine, uint16_t* __restrict__ xs) {
+    const int lanes = fine ? 8 : 16;
+    const int64_t G = K / (8 * lanes);
+    const int64_t unit = ((int64_t)blockIdx.x * 256 + threadIdx.x) / lanes;  // (m, g), g fastest
+    const int sub = threadIdx.x & (lanes - 1);
     const bool live = unit < M * G;
     const int64_t u = live ? unit : 0;
-    const uint4 v = reinterpret_cast<const uint4*>(x + u * kGroup)[sub];     // x is [M][G][128]
+    const uint4 v = reinterpret_cast<const uint4*>(x + u * (8 * lanes))[sub];    // x is [M][G][8 * lanes]
     float s = ((bf16lo_to_f32(v.x) + bf16hi_to_f32(v.x)) + (bf16lo_to_f32(v.y) + bf16hi_to_f32(v.y))) +
               ((bf16lo_to_f32(v.z) + bf16hi_to_f32(v.z)) + (bf16lo_to_f32(v.w) + bf16hi_to_f32(v.w)));
+    // rotations inside rows of 16 lanes: after 1, 2, 4 a lane holds the sum of itself and the 7 lanes
+    // before it (the last lane of a group of 8: its group); after 8, every lane holds the row's sum
     s += __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(s), 0x121, 0xF, 0xF, false));
     s += __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(s), 0x122, 0xF, 0xF, false));
     s += __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(s), 0x124, 0xF, 0xF, false));
-    s += __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(s), 0x128, 0xF, 0xF, false));
+    if (!fine) s += __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(s), 0x128, 0xF, 0xF, false));
     if (!live) return;
     const int64_t m = u / G, g = u % G;
-    if (sub == 0) {
+    if (sub == lanes - 1) {
         const uint32_t hi = f32_to_bf16(s);
         const uint32_t lo = f32_to_bf16(s - bf16_to_f32(hi));
         *reinterpret_cast<uint32_t*>(xs + m * KP + 2 * g) = hi | (lo << 16);
     }
     // zero padding of the row tail, done by the lanes of the row's last group
     if (g == G - 1)
-        for (int c = (int)(2 * G) + sub; c < KP; c += 16) xs[m * KP + c] = 0;
+        for (int c = (int)(2 * G) + sub; c < KP; c += lanes) xs[m * KP + c] = 0;
 }
 
 // LDS copy of the block's row tables, laid out so that the 32 lanes LDS serves together never share
 // a bank: a half-wavefront holds 8 rows x 4 quarter-threads, and entry c of (row, quarter) lives at
 // dword (row / 8) * (32 << BITS) + c * 32 + (row % 8) * 4 + quarter (every row is stored 4 times;
 // the bf16 value sits in the low half of the dword).
-template <int BITS>
+// FINE: groups of 64 weights - every K step is a group of its own (scale index 2g, 2g + 1 for the two
+// steps of chunk g; the offset phase runs over 64-weight groups).  Otherwise groups of 128 << lr.
+template <int BITS, bool FINE>
 __global__ __launch_bounds__(PTHREADS, 1) void prefill_kernel(
     const uint16_t* __restrict__ x, const uint32_t* __restrict__ codes,
     const uint16_t* __restrict__ lut, const uint16_t* __restrict__ scale,
@@ -133,8 +139,9 @@ __global__ __launch_bounds__(PTHREADS, 1) void prefill_kernel(
     for (int p = 0; p < 4; ++p) xsrc[p] = x + min(m0 + p * 64 + xr_row, M - 1) * K + xc8 * 8;
     // the two output columns this lane owns (one per 32-wide n tile of its wavefront)
     const uint16_t* scol[2];
+    const int64_t GS = FINE ? 2 * G : G >> lr;                            // scales / offsets per row
 #pragma unroll
-    for (int j = 0; j < 2; ++j) scol[j] = scale + min(n0 + wn * 64 + j * 32 + (lane & 31), N - 1) * (G >> lr);   // group of 128 << lr weights
+    for (int j = 0; j < 2; ++j) scol[j] = scale + min(n0 + wn * 64 + j * 32 + (lane & 31), N - 1) * GS;
     // LDS byte addresses (the kernel has no static LDS: dynamic LDS starts at 0)
     const uint32_t tbase = kTableOff + (uint32_t)((wrow >> 3) * (32 << BITS) + (wrow & 7) * 4 + wq) * 4u;
     const uint32_t xwr = (uint32_t)(xr_row * PLD + xc8 * 8) * 2u;                         // + buf * kXBuf + p * 64 rows
@@ -326,17 +333,27 @@ __global__ __launch_bounds__(PTHREADS, 1) void prefill_kernel(
     //      codes of step s + 3.  The last step stages a repeat of step T - 1 into a buffer that is
     //      not read again.
     for (int g = g_lo; g < g_hi; ++g) {
-        const uint32_t sraw0 = scol[0][g >> lr], sraw1 = scol[1][g >> lr];
         const int s = 2 * g;
-        step(B0{}, Yes{}, No{}, q1, min(s + 3, T - 1), min(s + 2, T - 1), 0u, 0u);
-        lds_barrier();
-        step(B1{}, No{}, Yes{}, q0, min(s + 4, T - 1), min(s + 3, T - 1), sraw0, sraw1);
-        lds_barrier();
+        if constexpr (FINE) {
+            // both scales of the chunk in one aligned 4-byte load per column
+            const uint32_t p0 = reinterpret_cast<const uint32_t*>(scol[0])[g], p1 = reinterpret_cast<const uint32_t*>(scol[1])[g];
+            step(B0{}, Yes{}, Yes{}, q1, min(s + 3, T - 1), min(s + 2, T - 1), p0 & 0xFFFFu, p1 & 0xFFFFu);
+            lds_barrier();
+            step(B1{}, Yes{}, Yes{}, q0, min(s + 4, T - 1), min(s + 3, T - 1), p0 >> 16, p1 >> 16);
+            lds_barrier();
+        } else {
+            const uint32_t sraw0 = scol[0][g >> lr], sraw1 = scol[1][g >> lr];
+            step(B0{}, Yes{}, No{}, q1, min(s + 3, T - 1), min(s + 2, T - 1), 0u, 0u);
+            lds_barrier();
+            step(B1{}, No{}, Yes{}, q0, min(s + 4, T - 1), min(s + 3, T - 1), sraw0, sraw1);
+            lds_barrier();
+        }
     }
 
     // ---- offset term: a few more K steps over the group dimension (activation group sums split into
     //      bf16 hi + lo in columns 2g, 2g+1; both columns meet offset[n][g]); unscaled
-    for (int k0 = 2 * g_lo / PBK * PBK; k0 < 2 * g_hi; k0 += PBK) {
+    const int og_lo = FINE ? 2 * g_lo : g_lo, og_hi = FINE ? 2 * g_hi : g_hi;      // this block's groups, in the units of xsums
+    for (int k0 = 2 * og_lo / PBK * PBK; k0 < 2 * og_hi; k0 += PBK) {
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
             const uint16_t* src = xsums + min(m0 + p * 64 + xr_row, M - 1) * KP + xc8 * 8 + k0;
@@ -346,7 +363,7 @@ __global__ __launch_bounds__(PTHREADS, 1) void prefill_kernel(
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const int gg = (k0 + wq * 16 + 2 * j) >> 1;
-            const uint32_t b = gg >= g_lo && gg < g_hi ? offset[wn_glob * (G >> lr) + (gg >> lr)] : 0u;
+            const uint32_t b = gg >= og_lo && gg < og_hi ? offset[wn_glob * GS + (FINE ? gg : gg >> lr)] : 0u;
             pk[j] = b | (b << 16);
         }
 #pragma unroll
@@ -444,7 +461,8 @@ PrefillPlan plan_prefill(int64_t M, int64_t N, int64_t K, int cus) {
         if (sl > G / 4) sl = G / 4;                            // at least four groups (eight K steps) per slice
         if (sl >= 2) { p.tail_tiles = r; p.tail_s = (int)sl; }
     }
-    p.xsums_bytes = ((size_t)M * (size_t)prefill_kp(K) * sizeof(uint16_t) + 255) / 256 * 256;
+    // (sized for groups of 64, the largest case: the workspace does not depend on the group size)
+    p.xsums_bytes = ((size_t)M * (size_t)prefill_kp(K, true) * sizeof(uint16_t) + 255) / 256 * 256;
     p.counter_bytes = p.tail_tiles ? splitk_counter_bytes(p.tail_tiles) : 0;
     p.partial_bytes = (size_t)p.tail_tiles * (size_t)p.tail_s * (PBM * PBN) * sizeof(float);
     return p;
@@ -460,32 +478,35 @@ hipError_t launch_prefill(const uint16_t* x, const uint32_t* codes, const uint16
                           int64_t M, int64_t N, int64_t K, int bits, int lr, bool repacked, int cus,
                           uint16_t* y, void* workspace, hipStream_t stream) {
     const PrefillPlan pp = plan_prefill(M, N, K, cus);
-    const int64_t units = M * (K / kGroup);
-    const int64_t sblocks = (units * 16 + 255) / 256;
+    const bool fine = lr < 0;
+    if (lr < -1) return hipErrorInvalidValue;
+    const int64_t sblocks = (M * (K / 8) + 255) / 256;         // one lane per 8 activations
     const int64_t nblocks = pp.tiles - pp.tail_tiles + pp.tail_tiles * pp.tail_s;
     if (pp.gm > 0x7FFFFFFF || nblocks > 0x7FFFFFFF || sblocks > 0x7FFFFFFF || K / kGroup > 0x1FFFFFFF) return hipErrorInvalidValue;
-    const int KP = prefill_kp(K);
+    const int KP = prefill_kp(K, fine);
     uint16_t* xsums = static_cast<uint16_t*>(workspace);
     unsigned long long* counters = reinterpret_cast<unsigned long long*>(static_cast<char*>(workspace) + pp.xsums_bytes);
     float* partial = reinterpret_cast<float*>(static_cast<char*>(workspace) + pp.xsums_bytes + pp.counter_bytes);
-    hipLaunchKernelGGL(group_sums_kernel, dim3((unsigned)sblocks), dim3(256), 0, stream, x, M, K, KP, xsums);
+    hipLaunchKernelGGL(group_sums_kernel, dim3((unsigned)sblocks), dim3(256), 0, stream, x, M, K, KP, fine ? 1 : 0, xsums);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const dim3 grid((unsigned)nblocks), block(PTHREADS);
     const int gm = (int)pp.gm, tail_first = (int)(pp.tiles - pp.tail_tiles), tail_s = pp.tail_s;
-#define ANY4_PREFILL(B)                                                                                           \
+#define ANY4_PREFILL_F(B, F)                                                                                      \
     do {                                                                                                          \
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(prefill_kernel<B>),                                 \
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(prefill_kernel<B, F>),                              \
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)prefill_lds_bytes(B));           \
         if (e != hipSuccess) return e;                                                                            \
-        hipLaunchKernelGGL(prefill_kernel<B>, grid, block, prefill_lds_bytes(B), stream, x, codes, lut, scale,    \
-                           offset, xsums, KP, M, N, K, lr, repacked ? 1 : 0, gm, tail_first, tail_s, counters, partial, y); \
+        hipLaunchKernelGGL((prefill_kernel<B, F>), grid, block, prefill_lds_bytes(B), stream, x, codes, lut, scale, \
+                           offset, xsums, KP, M, N, K, F ? 0 : lr, repacked ? 1 : 0, gm, tail_first, tail_s, counters, partial, y); \
     } while (0)
+#define ANY4_PREFILL(B) do { if (fine) ANY4_PREFILL_F(B, true); else ANY4_PREFILL_F(B, false); } while (0)
     switch (bits) {
         case 4: ANY4_PREFILL(4); break;
         case 3: ANY4_PREFILL(3); break;
         default: ANY4_PREFILL(2); break;
     }
+#undef ANY4_PREFILL_F
 #undef ANY4_PREFILL
     return hipGetLastError();
 }

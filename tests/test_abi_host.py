@@ -68,8 +68,8 @@ def test_bad_arguments_are_rejected_before_any_launch(lib):
     assert lib.any4_dequant(A, A, A, A, 4, 0, 4, A, None) == -2
     assert lib.any4_gemm(A, A, A, A, A, 0, 4, 128, 4, A, None, 0, None) == -2
     assert lib.any4_gemm(A, A, A, A, A, 1, 4, 192, 4, A, None, 0, None) == -2
-    # group sizes: 128, 256, 512, 1024 and a divisor of K
-    for group in (64, 192, 2048, 0):
+    # group sizes: 64, 128, 256, 512, 1024 and a divisor of K
+    for group in (32, 96, 192, 2048, 0):
         assert lib.any4_gemm_grouped(A, A, A, A, A, 1, 4, 2048, 4, group, A, None, 0, None) == -2
         assert lib.any4_dequant_grouped(A, A, A, A, 4, 2048, 4, group, A, None) == -2
     assert lib.any4_gemm_grouped(A, A, A, A, A, 1, 4, 640, 4, 256, A, None, 0, None) == -2

@@ -314,10 +314,69 @@ def test_gemm_grouped(any4, oracle, bits, group, M, N, K):
     check_gemm(y, y64, oracle.rms(y64), ("group", group, M, N, K, bits))
 
 
+def fine(M, N, K, bits, seed):
+    """a case with scales / offsets per 64 weights: two independent draws interleaved along K, so
+    that the two halves of every chunk of 128 carry unrelated values"""
+    a, b = inputs.make_case(M, N, K, bits, seed), inputs.make_case(1, N, K, bits, seed + 1000)
+    sc = np.ascontiguousarray(np.stack([a.scale, b.scale], axis=2).reshape(N, -1))
+    of = np.ascontiguousarray(np.stack([a.offset, b.offset], axis=2).reshape(N, -1))
+    return a, sc, of
+
+
+@pytest.mark.parametrize("bits", (4, 3, 2))
+@pytest.mark.parametrize("N,K", [(5, 128), (130, 2048), (17, 14336), (33, 640)])
+def test_dequant_groups_of_64_bit_exact(any4, oracle, bits, N, K):
+    cs, sc, of = fine(1, N, K, bits, inputs.case_seed(17, bits, N))
+    packed = oracle.pack(cs.codes_u8, bits)
+    w_ref = oracle.dequant(packed, cs.lut, sc, of, K, bits, group=64)
+    w = any4.any4_dequant(dev_codes(packed), dev_bf16(cs.lut), dev_bf16(sc), dev_bf16(of), K, bits, group=64)
+    torch.cuda.synchronize()
+    assert np.array_equal(w.cpu().numpy().view(np.uint32), w_ref.view(np.uint32))
+
+
+@pytest.mark.parametrize("bits", (4, 3, 2))
+@pytest.mark.parametrize("M,N,K", [(1, 16, 128), (1, 40, 1024), (2, 333, 4224), (3, 17, 384), (5, 333, 4096), (8, 700, 640),
+                                   (9, 100, 2048), (16, 100, 4480), (2, 64, 14336), (7, 40, 28672), (1, 2049, 1024),
+                                   (17, 128, 128), (32, 256, 4096), (100, 200, 1024), (129, 130, 640), (300, 130, 2048),
+                                   (260, 300, 8192)])
+def test_gemm_groups_of_64(any4, oracle, bits, M, N, K):
+    """Small M: the streaming kernel tells the halves of a chunk of 128 apart on the activation side,
+    8 rows a launch (one launch, two, one or several K slabs, ragged N).  Larger M: the matrix-core
+    kernel folds a scale in after every K step, whole tiles and K slices."""
+    cs, sc, of = fine(M, N, K, bits, inputs.case_seed(18, bits, M + N))
+    packed = oracle.pack(cs.codes_u8, bits)
+    y64 = oracle.gemm(cs.x, packed, cs.lut, sc, of, K, bits, threads=8, group=64)
+    y = any4.any4_gemm(dev_bf16(cs.x), dev_codes(packed), dev_bf16(cs.lut), dev_bf16(sc), dev_bf16(of), bits, group=64)
+    torch.cuda.synchronize()
+    check_gemm(y, y64, oracle.rms(y64), ("group 64", M, N, K, bits))
+
+
+def test_gemm_groups_of_64_with_doubled_scales_is_the_group_128_result(any4):
+    """every scale twice = groups of 128: the same sums, so the same bf16 output up to the order of
+    the fp32 additions (compared within one bf16 unit, most of them equal)"""
+    for M, N, K in ((4, 64, 2048), (64, 256, 1024)):
+        t = inputs.make_case_device(M, N, K, 4, seed=5, device=torch.device("cuda:0"))
+        codes = any4.any4_pack(t["codes_u8"], 4)
+        y128 = any4.any4_gemm(t["x"], codes, t["lut"], t["scale"], t["offset"], 4)
+        sc, of = t["scale"].repeat_interleave(2, dim=1).contiguous(), t["offset"].repeat_interleave(2, dim=1).contiguous()
+        y64 = any4.any4_gemm(t["x"], codes, t["lut"], sc, of, 4, group=64)
+        torch.cuda.synchronize()
+        a, b = y128.float(), y64.float()
+        assert torch.all((a - b).abs() <= 2.0 ** -7 * torch.maximum(a.abs(), b.abs()) + 1e-3)
+        assert (y128.view(torch.int16) == y64.view(torch.int16)).float().mean() > 0.9
+
+
+def test_groups_of_64_need_a_table_and_the_plain_layout(any4):
+    cs, sc, of = fine(1, 16, 256, 4, 3)
+    codes = any4.any4_pack(torch.from_numpy(cs.codes_u8).cuda(), 4)
+    with pytest.raises(any4.Any4Error):
+        any4.any4_gemm(dev_bf16(cs.x), codes, None, dev_bf16(sc), dev_bf16(of), 4, group=64)
+
+
 def test_grouped_rejects_other_group_sizes(any4):
     cs = inputs.make_case(1, 16, 1024, 4, 3)
     codes = any4.any4_pack(torch.from_numpy(cs.codes_u8).cuda(), 4)
-    for bad in (64, 192, 2048, 0, -128):
+    for bad in (32, 96, 192, 2048, 0, -128):
         with pytest.raises(any4.Any4Error):
             any4.any4_gemm(dev_bf16(cs.x), codes, dev_bf16(cs.lut), dev_bf16(cs.scale), dev_bf16(cs.offset), 4, group=bad)
     cs = inputs.make_case(1, 16, 640, 4, 3)                 # 640 is not a multiple of 256
