@@ -417,10 +417,14 @@ def main():
             fm[g["name"]] = {"any4_us": graph_us([call(p_, p_["lut"]) for p_ in rot]),
                              "shared_table_us": graph_us([call(p_, sh) for p_, sh in zip(rot, shared)]),
                              "int4_no_table_us": graph_us([call(p_, None) for p_ in rot])}
-            # other group sizes (section 2.5.1; the paper's Table 4 varies them): one scale per 256 / 1024 weights
-            for grp in (256, 1024):
+            # other group sizes (section 2.5.1; the paper's Table 4 varies them): one scale per 64 / 256 / 1024 weights
+            for grp in (64, 256, 1024):
                 r_ = grp // 128
-                coarse = [(p_["scale"][:, ::r_].contiguous(), p_["offset"][:, ::r_].contiguous()) for p_ in rot]
+                if grp == 64:
+                    coarse = [(p_["scale"].repeat_interleave(2, dim=1).contiguous(),
+                               p_["offset"].repeat_interleave(2, dim=1).contiguous()) for p_ in rot]
+                else:
+                    coarse = [(p_["scale"][:, ::r_].contiguous(), p_["offset"][:, ::r_].contiguous()) for p_ in rot]
                 fm[g["name"]][f"any4_group{grp}_us"] = graph_us(
                     [(lambda p_=p_, c_=c_: any4.any4_gemm(p_["x"], p_["codes"], p_["lut"], c_[0], c_[1], bits, out=p_["y"],
                                                           workspace=p_["ws"], group=grp)) for p_, c_ in zip(rot, coarse)])
