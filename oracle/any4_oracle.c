@@ -34,6 +34,8 @@
  * Group sizes other than 128 (the *_g functions): expanding the scales to one per 128 weights
  * (or, for groups of 64, to one per 64) must give the finer-group result bit for bit, a single
  * group per row has a closed form, groups of 64 are checked block by block against numpy.
+ * fp16 storage (the *_gd functions with f16 != 0): the widening is checked on all 65536 patterns
+ * against numpy's float16, the GEMM against a library fp64 matmul of the widened arrays.
  * The tile-major re-layout (any4o_repack) is pinned by a word-level transpose written
  * with numpy, by reading single codes back out of it, by its zero padding and by the
  * multiset of its words.
@@ -51,6 +53,20 @@ static float bf16_bits_to_float(uint16_t b) {
     memcpy(&f, &u, sizeof f);
     return f;
 }
+
+/* IEEE binary16 bit pattern -> float, from the format's definition: 1 sign, 5 exponent (bias 15),
+ * 10 fraction bits; exponent 0 = zero / subnormal (fraction * 2^-24), 31 = infinity / NaN */
+float any4o_f16_bits_to_float(uint16_t h) {
+    uint32_t sign = (h >> 15) & 1u, e = (h >> 10) & 31u, m = h & 1023u;
+    float v;
+    if (e == 0) v = ldexpf((float)m, -24);
+    else if (e == 31) v = m ? NAN : INFINITY;
+    else v = ldexpf((float)(m + 1024u), (int)e - 25);
+    return sign ? -v : v;
+}
+
+/* 16-bit storage -> float: bf16, or fp16 (section 2.4.1 names both for the table) */
+static float widen(uint16_t b, int f16) { return f16 ? any4o_f16_bits_to_float(b) : bf16_bits_to_float(b); }
 
 static int bits_ok(int bits) { return bits == 2 || bits == 3 || bits == 4; }
 
@@ -133,8 +149,9 @@ static int group_ok(int64_t K, int64_t group) {
 
 /* the same with a group of `group` weights (a multiple of 64 that divides K; the paper's
  * Table 4 varies the group size from 64 to 1024): scale / offset are [N][K / group] */
-int64_t any4o_dequant_g(const uint32_t *packed, const uint16_t *lut, const uint16_t *scale,
-                        const uint16_t *offset, int64_t N, int64_t K, int bits, int64_t group, float *w) {
+/* f16 != 0: table, scale and offset (and the activations of the GEMM) are fp16 instead of bf16 */
+int64_t any4o_dequant_gd(const uint32_t *packed, const uint16_t *lut, const uint16_t *scale,
+                         const uint16_t *offset, int64_t N, int64_t K, int bits, int64_t group, int f16, float *w) {
     if (!packed || !lut || !scale || !offset || !w || N < 1 || K < 1 || K % ANY4O_GROUP || !bits_ok(bits) ||
         !group_ok(K, group))
         return -1;
@@ -143,9 +160,9 @@ int64_t any4o_dequant_g(const uint32_t *packed, const uint16_t *lut, const uint1
     for (int64_t n = 0; n < N; ++n) {
         for (int64_t k = 0; k < K; ++k) {
             uint32_t c = any4o_code(packed + n * W, k, bits);
-            float v = bf16_bits_to_float(lut[n * L + c]);
-            float s = bf16_bits_to_float(scale[n * G + k / group]);
-            float o = bf16_bits_to_float(offset[n * G + k / group]);
+            float v = widen(lut[n * L + c], f16);
+            float s = widen(scale[n * G + k / group], f16);
+            float o = widen(offset[n * G + k / group], f16);
             float fused = fmaf(v, s, o);
             volatile float prod = v * s;              /* force the intermediate rounding */
             volatile float two_step = prod + o;
@@ -157,6 +174,11 @@ int64_t any4o_dequant_g(const uint32_t *packed, const uint16_t *lut, const uint1
     return differ;
 }
 
+int64_t any4o_dequant_g(const uint32_t *packed, const uint16_t *lut, const uint16_t *scale,
+                        const uint16_t *offset, int64_t N, int64_t K, int bits, int64_t group, float *w) {
+    return any4o_dequant_gd(packed, lut, scale, offset, N, K, bits, group, 0, w);
+}
+
 int64_t any4o_dequant(const uint32_t *packed, const uint16_t *lut, const uint16_t *scale,
                       const uint16_t *offset, int64_t N, int64_t K, int bits, float *w) {
     return any4o_dequant_g(packed, lut, scale, offset, N, K, bits, ANY4O_GROUP, w);
@@ -165,9 +187,9 @@ int64_t any4o_dequant(const uint32_t *packed, const uint16_t *lut, const uint16_
 /* y[m][n] = sum_{k=0..K-1} (double)w[n][k] * (double)x[m][k], k ascending, fp64.
  * `threads` > 1 only distributes whole output rows n over OpenMP threads; the
  * arithmetic of every output element is unchanged.  Returns 0 or -1. */
-int any4o_gemm_g(const uint16_t *x, const uint32_t *packed, const uint16_t *lut, const uint16_t *scale,
-                 const uint16_t *offset, int64_t M, int64_t N, int64_t K, int bits, int64_t group,
-                 double *y, int threads) {
+int any4o_gemm_gd(const uint16_t *x, const uint32_t *packed, const uint16_t *lut, const uint16_t *scale,
+                  const uint16_t *offset, int64_t M, int64_t N, int64_t K, int bits, int64_t group, int f16,
+                  double *y, int threads) {
     if (!x || !packed || !lut || !scale || !offset || !y || M < 1 || N < 1 || K < 1 ||
         K % ANY4O_GROUP || !bits_ok(bits) || !group_ok(K, group))
         return -1;
@@ -180,21 +202,27 @@ int any4o_gemm_g(const uint16_t *x, const uint32_t *packed, const uint16_t *lut,
         for (int64_t n = 0; n < N; ++n) {
             for (int64_t k = 0; k < K; ++k) {
                 uint32_t c = any4o_code(packed + n * W, k, bits);
-                float v = bf16_bits_to_float(lut[n * L + c]);
-                float s = bf16_bits_to_float(scale[n * G + k / group]);
-                float o = bf16_bits_to_float(offset[n * G + k / group]);
+                float v = widen(lut[n * L + c], f16);
+                float s = widen(scale[n * G + k / group], f16);
+                float o = widen(offset[n * G + k / group], f16);
                 wrow[k] = fmaf(v, s, o);
             }
             for (int64_t m = 0; m < M; ++m) {
                 double acc = 0.0;
                 for (int64_t k = 0; k < K; ++k)
-                    acc += (double)wrow[k] * (double)bf16_bits_to_float(x[m * K + k]);
+                    acc += (double)wrow[k] * (double)widen(x[m * K + k], f16);
                 y[m * N + n] = acc;
             }
         }
         free(wrow);
     }
     return 0;
+}
+
+int any4o_gemm_g(const uint16_t *x, const uint32_t *packed, const uint16_t *lut, const uint16_t *scale,
+                 const uint16_t *offset, int64_t M, int64_t N, int64_t K, int bits, int64_t group,
+                 double *y, int threads) {
+    return any4o_gemm_gd(x, packed, lut, scale, offset, M, N, K, bits, group, 0, y, threads);
 }
 
 int any4o_gemm(const uint16_t *x, const uint32_t *packed, const uint16_t *lut, const uint16_t *scale,

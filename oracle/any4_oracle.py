@@ -50,6 +50,12 @@ def _load():
         lib.any4o_dequant_g.argtypes = [p, p, p, p, i64, i64, ctypes.c_int, i64, p]
         lib.any4o_gemm_g.restype = ctypes.c_int
         lib.any4o_gemm_g.argtypes = [p, p, p, p, p, i64, i64, i64, ctypes.c_int, i64, p, ctypes.c_int]
+        lib.any4o_dequant_gd.restype = i64
+        lib.any4o_dequant_gd.argtypes = [p, p, p, p, i64, i64, ctypes.c_int, i64, ctypes.c_int, p]
+        lib.any4o_gemm_gd.restype = ctypes.c_int
+        lib.any4o_gemm_gd.argtypes = [p, p, p, p, p, i64, i64, i64, ctypes.c_int, i64, ctypes.c_int, p, ctypes.c_int]
+        lib.any4o_f16_bits_to_float.restype = ctypes.c_float
+        lib.any4o_f16_bits_to_float.argtypes = [ctypes.c_uint16]
         lib.any4o_rms.restype = ctypes.c_double
         lib.any4o_rms.argtypes = [p, i64]
         lib.any4o_bits_per_weight.restype = ctypes.c_double
@@ -108,9 +114,15 @@ def unpack(packed: np.ndarray, K: int, bits: int) -> np.ndarray:
     return out
 
 
-def dequant(packed, lut, scale, offset, K: int, bits: int, return_differ: bool = False, group: int = GROUP):
+def f16_bits_to_float(h: int) -> float:
+    return float(_load().any4o_f16_bits_to_float(int(h)))
+
+
+def dequant(packed, lut, scale, offset, K: int, bits: int, return_differ: bool = False, group: int = GROUP,
+            f16: bool = False):
     """fp32 [N,K] dequantised weights; optionally also the count of elements whose
-    fused and two-step roundings differ (expected 0).  scale / offset are [N, K / group]."""
+    fused and two-step roundings differ (expected 0 for bf16 storage).  scale / offset are
+    [N, K / group]; f16: the 16-bit inputs are fp16 bit patterns instead of bf16."""
     N = packed.shape[0]
     a, pa = _c(packed, np.uint32)
     b, pb = _c(lut, np.uint16)
@@ -119,14 +131,16 @@ def dequant(packed, lut, scale, offset, K: int, bits: int, return_differ: bool =
     w = np.empty((N, K), dtype=np.float32)
     if c.shape != (N, K // group) or d.shape != (N, K // group):
         raise ValueError("scale / offset must be [N, K / group]")
-    differ = _load().any4o_dequant_g(pa, pb, pc, pd, N, K, bits, group, w.ctypes.data_as(ctypes.c_void_p))
+    differ = _load().any4o_dequant_gd(pa, pb, pc, pd, N, K, bits, group, 1 if f16 else 0, w.ctypes.data_as(ctypes.c_void_p))
     if differ < 0:
         raise ValueError("any4o_dequant: bad arguments")
     return (w, int(differ)) if return_differ else w
 
 
-def gemm(x, packed, lut, scale, offset, K: int, bits: int, threads: int = 1, group: int = GROUP) -> np.ndarray:
-    """fp64 [M,N] = x[M,K] . dequant(...)[N,K]^T, sequential in k.  scale / offset are [N, K / group]."""
+def gemm(x, packed, lut, scale, offset, K: int, bits: int, threads: int = 1, group: int = GROUP,
+         f16: bool = False) -> np.ndarray:
+    """fp64 [M,N] = x[M,K] . dequant(...)[N,K]^T, sequential in k.  scale / offset are [N, K / group];
+    f16: the 16-bit inputs are fp16 bit patterns instead of bf16."""
     N = packed.shape[0]
     M = x.shape[0]
     xx, px = _c(x, np.uint16)
@@ -137,7 +151,8 @@ def gemm(x, packed, lut, scale, offset, K: int, bits: int, threads: int = 1, gro
     y = np.empty((M, N), dtype=np.float64)
     if c.shape != (N, K // group) or d.shape != (N, K // group):
         raise ValueError("scale / offset must be [N, K / group]")
-    rc = _load().any4o_gemm_g(px, pa, pb, pc, pd, M, N, K, bits, group, y.ctypes.data_as(ctypes.c_void_p), threads)
+    rc = _load().any4o_gemm_gd(px, pa, pb, pc, pd, M, N, K, bits, group, 1 if f16 else 0,
+                               y.ctypes.data_as(ctypes.c_void_p), threads)
     if rc != 0:
         raise ValueError("any4o_gemm: bad arguments")
     return y

@@ -14,7 +14,7 @@ model, paper section 5 "Results", first paragraph):
   offset  N(0, 0.002)     per (row, 128-wide group along K), bf16 [N, K/128]
   x       N(0, 1) activations, bf16 [M, K]
 Draw order with numpy's PCG64 `default_rng(seed)`: codes, lut, scale, offset, x.
-bf16 tensors are carried as uint16 bit patterns.
+bf16 tensors are carried as uint16 bit patterns.  With f16=True the same draws are stored as fp16.
 """
 from __future__ import annotations
 
@@ -47,6 +47,16 @@ def f32_to_bf16_bits(a: np.ndarray) -> np.ndarray:
     return ((u + bias) >> np.uint32(16)).astype(np.uint16)
 
 
+def f32_to_f16_bits(a: np.ndarray) -> np.ndarray:
+    """Round fp32 values to fp16 (numpy's conversion: round-to-nearest-even), uint16 bit patterns."""
+    return np.ascontiguousarray(a, dtype=np.float32).astype(np.float16).view(np.uint16)
+
+
+def f16_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    """Widen fp16 bit patterns to fp32 (exact)."""
+    return np.ascontiguousarray(b, dtype=np.uint16).view(np.float16).astype(np.float32)
+
+
 def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
     """Widen bf16 bit patterns to fp32 (exact)."""
     return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
@@ -72,7 +82,8 @@ def case_seed(base_seed: int, shape_index: int = 0, m_index: int = 0) -> int:
     return base_seed * 1000 + shape_index * 10 + m_index
 
 
-def make_case(M: int, N: int, K: int, bits: int = 4, seed: int = 0) -> Case:
+def make_case(M: int, N: int, K: int, bits: int = 4, seed: int = 0, f16: bool = False) -> Case:
+    """f16: the same draws stored as fp16 bit patterns (the paper's other 16-bit type, section 2.4.1)"""
     if K % GROUP != 0:
         raise ValueError("K must be a multiple of 128")
     if bits not in (2, 3, 4):
@@ -85,12 +96,11 @@ def make_case(M: int, N: int, K: int, bits: int = 4, seed: int = 0) -> Case:
     scale = rng.uniform(0.005, 0.02, size=(N, G)).astype(np.float32)
     offset = (rng.standard_normal((N, G), dtype=np.float32) * np.float32(0.002))
     x = rng.standard_normal((M, K), dtype=np.float32)
-    return Case(M, N, K, bits, seed, codes,
-                f32_to_bf16_bits(lut), f32_to_bf16_bits(scale),
-                f32_to_bf16_bits(offset), f32_to_bf16_bits(x))
+    store = f32_to_f16_bits if f16 else f32_to_bf16_bits
+    return Case(M, N, K, bits, seed, codes, store(lut), store(scale), store(offset), store(x))
 
 
-def make_case_device(M: int, N: int, K: int, bits: int = 4, seed: int = 0, device="cuda"):
+def make_case_device(M: int, N: int, K: int, bits: int = 4, seed: int = 0, device="cuda", f16: bool = False):
     """Same distributions drawn with torch's generator directly in device memory,
     for the full-size benchmark shapes (hundreds of MB of codes).  Returns a dict of
     torch tensors: codes_u8 uint8 [N,K]; lut/scale/offset/x as bf16 tensors."""
@@ -104,12 +114,13 @@ def make_case_device(M: int, N: int, K: int, bits: int = 4, seed: int = 0, devic
     scale = torch.empty((N, G), dtype=torch.float32, device=device).uniform_(0.005, 0.02, generator=g)
     offset = torch.randn((N, G), dtype=torch.float32, device=device, generator=g) * 0.002
     x = torch.randn((M, K), dtype=torch.float32, device=device, generator=g)
+    dt = torch.float16 if f16 else torch.bfloat16
     return {
         "codes_u8": codes,
-        "lut": lut.to(torch.bfloat16),
-        "scale": scale.to(torch.bfloat16),
-        "offset": offset.to(torch.bfloat16),
-        "x": x.to(torch.bfloat16),
+        "lut": lut.to(dt),
+        "scale": scale.to(dt),
+        "offset": offset.to(dt),
+        "x": x.to(dt),
     }
 
 
