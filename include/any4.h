@@ -102,6 +102,23 @@ int any4_gemm(const uint16_t* x, const uint32_t* codes, const uint16_t* lut,
 size_t any4_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int bits);
 
 /*
+ * any4_dequant_f16 / any4_gemm_f16 - the same two operations with IEEE fp16 in place of bf16
+ * (section 2.4.1 names bfloat16 and float16 as the types of the table entries): lut, scale, offset,
+ * x and y are fp16 bit patterns; the products and sums are fp32 as before, w is fp32, y is
+ * rounded to fp16 (nearest even).  Groups of 128, plain code layout, a table is required
+ * (lut == NULL returns ANY4_ERR_NULL).  Shapes, alignment, workspace (any4_gemm_workspace_bytes)
+ * and error behaviour are those of any4_dequant / any4_gemm; for M <= 16, K > 262144 returns
+ * ANY4_ERR_SHAPE.  The sums of 128 consecutive activations must stay inside the fp16 range
+ * (|sum| < 65504): they pass through fp16 pairs on their way to the matrix cores.
+ */
+int any4_dequant_f16(const uint32_t* codes, const uint16_t* lut, const uint16_t* scale,
+                     const uint16_t* offset, int64_t N, int64_t K, int bits, float* w, void* stream);
+int any4_gemm_f16(const uint16_t* x, const uint32_t* codes, const uint16_t* lut,
+                  const uint16_t* scale, const uint16_t* offset,
+                  int64_t M, int64_t N, int64_t K, int bits,
+                  uint16_t* y, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * any4_dequant_grouped / any4_gemm_grouped - the same two operations with a scale and an offset
  * shared by `group` consecutive weights along K instead of 128 (section 2.5.1, "Groupwise"; the
  * paper's Table 4 varies the group size): scale and offset are bf16 [N][K/group].

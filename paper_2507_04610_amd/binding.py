@@ -16,7 +16,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libany4.so")
 GROUP = 128
 
-EXPORTS = ("any4_pack", "any4_dequant", "any4_gemm", "any4_gemm_workspace_bytes", "any4_repack", "any4_repack_bytes", "any4_gemm_repacked", "any4_dequant_grouped", "any4_gemm_grouped",
+EXPORTS = ("any4_pack", "any4_dequant", "any4_gemm", "any4_gemm_workspace_bytes", "any4_repack", "any4_repack_bytes", "any4_gemm_repacked", "any4_dequant_grouped", "any4_gemm_grouped", "any4_dequant_f16", "any4_gemm_f16",
            "any4_quantize", "any4_quantize_max_k", "any4_stream_read", "any4_strerror", "any4_version")
 
 
@@ -47,6 +47,10 @@ def load_library() -> ctypes.CDLL:
     lib.any4_gemm_workspace_bytes.argtypes = [i64, i64, i64, ci]
     lib.any4_dequant_grouped.restype = ci
     lib.any4_dequant_grouped.argtypes = [vp, vp, vp, vp, i64, i64, ci, ci, vp, vp]
+    lib.any4_dequant_f16.restype = ci
+    lib.any4_dequant_f16.argtypes = [vp, vp, vp, vp, i64, i64, ci, vp, vp]
+    lib.any4_gemm_f16.restype = ci
+    lib.any4_gemm_f16.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, ci, vp, vp, ctypes.c_size_t, vp]
     lib.any4_gemm_grouped.restype = ci
     lib.any4_gemm_grouped.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, ci, ci, vp, vp, ctypes.c_size_t, vp]
     lib.any4_gemm_repacked.restype = ci
@@ -120,17 +124,23 @@ def any4_pack(codes_u8: torch.Tensor, bits: int = 4, out: torch.Tensor | None = 
 def any4_dequant(codes: torch.Tensor, lut: torch.Tensor | None, scale: torch.Tensor, offset: torch.Tensor,
                  K: int, bits: int = 4, out: torch.Tensor | None = None, group: int = GROUP) -> torch.Tensor:
     """fp32 [N,K] dequantised weights (lut None with bits 4: the int4 grid, value = code - 8);
-    scale / offset are [N, K / group] (any4_dequant_grouped when group is not 128)."""
+    scale / offset are [N, K / group] (any4_dequant_grouped when group is not 128).
+    lut / scale / offset are bf16, or all fp16 (any4_dequant_f16: groups of 128, a table)."""
     lib = load_library()
     N = codes.shape[0]
     pc = _dev(codes, torch.int32, "codes")
-    pl = _dev(lut, torch.bfloat16, "lut") if lut is not None else None
-    ps = _dev(scale, torch.bfloat16, "scale")
-    po = _dev(offset, torch.bfloat16, "offset")
+    dt = scale.dtype if isinstance(scale, torch.Tensor) and scale.dtype == torch.float16 else torch.bfloat16
+    pl = _dev(lut, dt, "lut") if lut is not None else None
+    ps = _dev(scale, dt, "scale")
+    po = _dev(offset, dt, "offset")
     if out is None:
         out = torch.empty((N, K), dtype=torch.float32, device=codes.device)
     pw = _dev(out, torch.float32, "out")
-    if group == GROUP:
+    if dt == torch.float16:
+        if group != GROUP:
+            raise Any4Error("fp16 inputs come with groups of 128")
+        _check(lib.any4_dequant_f16(pc, pl, ps, po, N, K, bits, pw, _stream()), "any4_dequant_f16")
+    elif group == GROUP:
         _check(lib.any4_dequant(pc, pl, ps, po, N, K, bits, pw, _stream()), "any4_dequant")
     else:
         _check(lib.any4_dequant_grouped(pc, pl, ps, po, N, K, bits, group, pw, _stream()), "any4_dequant_grouped")
@@ -140,14 +150,19 @@ def any4_dequant(codes: torch.Tensor, lut: torch.Tensor | None, scale: torch.Ten
 def _gemm(entry: str, x, codes, N, lut, scale, offset, bits, out, workspace, group=None):
     lib = load_library()
     M, K = x.shape
-    px = _dev(x, torch.bfloat16, "x")
+    dt = x.dtype if isinstance(x, torch.Tensor) and x.dtype == torch.float16 else torch.bfloat16
+    if dt == torch.float16:
+        if entry != "any4_gemm":
+            raise Any4Error("fp16 inputs come with groups of 128 and the plain code layout")
+        entry = "any4_gemm_f16"
+    px = _dev(x, dt, "x")
     pc = _dev(codes, torch.int32, "codes")
-    pl = _dev(lut, torch.bfloat16, "lut") if lut is not None else None
-    ps = _dev(scale, torch.bfloat16, "scale")
-    po = _dev(offset, torch.bfloat16, "offset")
+    pl = _dev(lut, dt, "lut") if lut is not None else None
+    ps = _dev(scale, dt, "scale")
+    po = _dev(offset, dt, "offset")
     if out is None:
-        out = torch.empty((M, N), dtype=torch.bfloat16, device=x.device)
-    py = _dev(out, torch.bfloat16, "out")
+        out = torch.empty((M, N), dtype=dt, device=x.device)
+    py = _dev(out, dt, "out")
     need = int(lib.any4_gemm_workspace_bytes(M, N, K, bits))
     if workspace is None and need > 0:
         workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
@@ -165,7 +180,8 @@ def any4_gemm(x: torch.Tensor, codes: torch.Tensor, lut: torch.Tensor | None, sc
               workspace: torch.Tensor | None = None, group: int = GROUP) -> torch.Tensor:
     """bf16 [M,N] = x[M,K] . dequant(codes, lut, scale, offset)[N,K]^T
     (lut None with bits 4: the int4 grid, value = code - 8, run without a table);
-    scale / offset are [N, K / group] (any4_gemm_grouped when group is not 128)."""
+    scale / offset are [N, K / group] (any4_gemm_grouped when group is not 128).
+    With x, lut, scale, offset all fp16 the result is fp16 (any4_gemm_f16: groups of 128, a table)."""
     if group == GROUP:
         return _gemm("any4_gemm", x, codes, codes.shape[0], lut, scale, offset, bits, out, workspace)
     return _gemm("any4_gemm_grouped", x, codes, codes.shape[0], lut, scale, offset, bits, out, workspace, group)

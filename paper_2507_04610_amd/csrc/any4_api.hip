@@ -128,7 +128,17 @@ int any4_dequant_grouped(const uint32_t* codes, const uint16_t* lut, const uint1
     if (!group_shift(K, group, &lr)) return ANY4_ERR_SHAPE;
     if (!aligned16(codes) || !aligned16(lut) || !aligned16(scale) || !aligned16(offset) || !aligned16(w))
         return ANY4_ERR_ALIGN;
-    return launch_dequant(codes, lut, scale, offset, N, K, bits, lr, w, static_cast<hipStream_t>(stream)) == hipSuccess
+    return launch_dequant(codes, lut, scale, offset, N, K, bits, lr, false, w, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? ANY4_OK : ANY4_ERR_HIP;
+}
+
+int any4_dequant_f16(const uint32_t* codes, const uint16_t* lut, const uint16_t* scale,
+                     const uint16_t* offset, int64_t N, int64_t K, int bits, float* w, void* stream) {
+    if (!codes || !lut || !scale || !offset || !w) return ANY4_ERR_NULL;
+    if (int rc = shape_check(N, K, bits)) return rc;
+    if (!aligned16(codes) || !aligned16(lut) || !aligned16(scale) || !aligned16(offset) || !aligned16(w))
+        return ANY4_ERR_ALIGN;
+    return launch_dequant(codes, lut, scale, offset, N, K, bits, 0, true, w, static_cast<hipStream_t>(stream)) == hipSuccess
                ? ANY4_OK : ANY4_ERR_HIP;
 }
 
@@ -168,8 +178,10 @@ size_t any4_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int bits) {
 
 static int gemm_any_layout(const uint16_t* x, const uint32_t* codes, bool repacked, const uint16_t* lut,
                            const uint16_t* scale, const uint16_t* offset, int64_t M, int64_t N, int64_t K,
-                           int bits, int group, uint16_t* y, void* workspace, size_t workspace_bytes, void* stream) {
+                           int bits, int group, uint16_t* y, void* workspace, size_t workspace_bytes, void* stream,
+                           bool f16 = false) {
     if (!x || !codes || !scale || !offset || !y) return ANY4_ERR_NULL;
+    if (f16 && !lut) return ANY4_ERR_NULL;                           // fp16: table-based only
     if (!lut && (bits != 4 || repacked)) return ANY4_ERR_NULL;       // no table = the 4-bit integer grid, plain layout only
     if (int rc = shape_check(N, K, bits)) return rc;
     if (M < 1) return ANY4_ERR_SHAPE;
@@ -181,7 +193,7 @@ static int gemm_any_layout(const uint16_t* x, const uint32_t* codes, bool repack
         return ANY4_ERR_ALIGN;
     const GemmPlan plan = plan_gemm(M, N, K, bits);
     // K beyond the streaming kernel's range: only the plain layout with groups of 128
-    if ((repacked || lr != 0) && plan.decode && !plan.stream) return ANY4_ERR_SHAPE;
+    if ((repacked || lr != 0 || f16) && plan.decode && !plan.stream) return ANY4_ERR_SHAPE;
     if (plan.workspace > 0 && (!workspace || workspace_bytes < plan.workspace)) return ANY4_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t e;
@@ -190,25 +202,25 @@ static int gemm_any_layout(const uint16_t* x, const uint32_t* codes, bool repack
         e = hipSuccess;
         for (int64_t m0 = 0; m0 < M && e == hipSuccess; m0 += kFineRows) {
             const int64_t rows = M - m0 < kFineRows ? M - m0 : kFineRows;
-            e = launch_decode_stream(x + m0 * K, codes, lut, scale, offset, rows, N, K, bits, lr, false, plan.sp,
+            e = launch_decode_stream(x + m0 * K, codes, lut, scale, offset, rows, N, K, bits, lr, false, false, plan.sp,
                                      y + m0 * N, workspace, s);
         }
     } else if (lr < 0) {
-        e = launch_prefill(x, codes, lut, scale, offset, M, N, K, bits, lr, false, device_compute_units(), y, workspace, s);
+        e = launch_prefill(x, codes, lut, scale, offset, M, N, K, bits, lr, false, false, device_compute_units(), y, workspace, s);
     } else if (plan.chunked) {
         // launches run one after the other on the stream and leave the workspace's counters clean
         e = hipSuccess;
         for (int64_t m0 = 0; m0 < M && e == hipSuccess; m0 += kStreamMaxM) {
             const int64_t rows = M - m0 < kStreamMaxM ? M - m0 : kStreamMaxM;
-            e = launch_decode_stream(x + m0 * K, codes, lut, scale, offset, rows, N, K, bits, lr, repacked,
+            e = launch_decode_stream(x + m0 * K, codes, lut, scale, offset, rows, N, K, bits, lr, repacked, f16,
                                      rows == kStreamMaxM ? plan.sp : plan.sp_tail, y + m0 * N, workspace, s);
         }
     } else if (plan.stream) {
-        e = launch_decode_stream(x, codes, lut, scale, offset, M, N, K, bits, lr, repacked, plan.sp, y, workspace, s);
+        e = launch_decode_stream(x, codes, lut, scale, offset, M, N, K, bits, lr, repacked, f16, plan.sp, y, workspace, s);
     } else if (plan.decode) {
         e = launch_decode(x, codes, lut, scale, offset, M, N, K, bits, plan, y, static_cast<float*>(workspace), s);
     } else {
-        e = launch_prefill(x, codes, lut, scale, offset, M, N, K, bits, lr, repacked, device_compute_units(), y, workspace, s);
+        e = launch_prefill(x, codes, lut, scale, offset, M, N, K, bits, lr, repacked, f16, device_compute_units(), y, workspace, s);
     }
     return e == hipSuccess ? ANY4_OK : ANY4_ERR_HIP;
 }
@@ -217,6 +229,12 @@ int any4_gemm(const uint16_t* x, const uint32_t* codes, const uint16_t* lut, con
               const uint16_t* offset, int64_t M, int64_t N, int64_t K, int bits, uint16_t* y,
               void* workspace, size_t workspace_bytes, void* stream) {
     return gemm_any_layout(x, codes, false, lut, scale, offset, M, N, K, bits, ANY4_GROUP, y, workspace, workspace_bytes, stream);
+}
+
+int any4_gemm_f16(const uint16_t* x, const uint32_t* codes, const uint16_t* lut, const uint16_t* scale,
+                  const uint16_t* offset, int64_t M, int64_t N, int64_t K, int bits, uint16_t* y,
+                  void* workspace, size_t workspace_bytes, void* stream) {
+    return gemm_any_layout(x, codes, false, lut, scale, offset, M, N, K, bits, ANY4_GROUP, y, workspace, workspace_bytes, stream, true);
 }
 
 int any4_gemm_grouped(const uint16_t* x, const uint32_t* codes, const uint16_t* lut, const uint16_t* scale,

@@ -68,7 +68,14 @@
 namespace any4 {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// D = A (16 x 32) * B (32 x 16) + C with eight 16-bit values per lane and operand
+template <bool F16> __device__ __forceinline__ f32x4 mfma16(const uint4& a, const uint4& b, const f32x4& c) {
+    if constexpr (F16) return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    else return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
 
 namespace stream {
 
@@ -157,8 +164,11 @@ __device__ __forceinline__ float sum8(const uint4& v) {
 //         halves sit in the k-slots of quarter 0 (rows < 8) and those of the second halves in the
 //         slots of quarter 1 (rows >= 8), facing the two offsets.  Rows m and m + 8 are added
 //         when the wavefronts' partial sums are.
-template <int BITS, int GW, bool AUX, bool NOLUT, bool REPACK, bool COARSE, bool FINE>
+// F16     activations, table, scales, offsets and output are fp16 instead of bf16 (the f16 matrix
+//         instruction; everything else moves 16-bit patterns and does not care)
+template <int BITS, int GW, bool AUX, bool NOLUT, bool REPACK, bool COARSE, bool FINE, bool F16>
 __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Params p) {
+    static_assert(!F16 || (!NOLUT && !REPACK && !COARSE && !FINE), "fp16: table-based, plain layout, groups of 128");
     static_assert(!COARSE || (!NOLUT && !REPACK), "groups above 128 weights: table-based, plain layout");
     static_assert(!FINE || (!COARSE && !NOLUT && !REPACK), "groups of 64 weights: table-based, plain layout");
     static_assert(!(FINE && AUX && BITS == 2), "the larger slots of the shared small inputs do not fit beside the any2 tables");
@@ -458,7 +468,7 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
             if (gi < ngw) { sp[gi >> 1] |= sr[gi] << (16 * (gi & 1)); op[gi >> 1] |= orw[gi] << (16 * (gi & 1)); }
     };
     auto scale_f = [&](const uint32_t (&sp)[NP], int gi) -> float {
-        return (gi & 1) ? bf16hi_to_f32(sp[gi >> 1]) : bf16lo_to_f32(sp[gi >> 1]);
+        return (gi & 1) ? h16hi_to_f32<F16>(sp[gi >> 1]) : h16lo_to_f32<F16>(sp[gi >> 1]);
     };
     // offsets of the wavefront's groups as a B operand: k-slots 0..3 and 4..7 both hold o[g0..g3]
     // (slots of groups the wavefront does not have are zero and meet zero activation sums)
@@ -578,7 +588,8 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
     // the lanes of column m (the lanes that hold row m of x) receive exactly their own row's sum.
     uint4 xo;
     {
-        const uint4 ones = make_uint4(0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u);
+        constexpr uint32_t one2 = F16 ? 0x3C003C00u : 0x3F803F80u;      // 1.0 twice
+        const uint4 ones = make_uint4(one2, one2, one2, one2);
         const f32x4 z4 = {0.f, 0.f, 0.f, 0.f};
         f32x4 gs[GW];
 #pragma unroll
@@ -587,14 +598,13 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
         for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int gi = 0; gi < GW; ++gi)
-                gs[gi] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ones),
-                                                                 __builtin_bit_cast(bf16x8, xa[gi][j]), gs[gi], 0, 0, 0);
+                gs[gi] = mfma16<F16>(ones, xa[gi][j], gs[gi]);
         uint32_t hi[4] = {0, 0, 0, 0}, lo[4] = {0, 0, 0, 0};
 #pragma unroll
         for (int gi = 0; gi < GW; ++gi) {
             const float sgi = gs[gi][0];
-            hi[gi] = f32_to_bf16(sgi);
-            lo[gi] = f32_to_bf16(sgi - bf16_to_f32(hi[gi]));
+            hi[gi] = f32_to_h16<F16>(sgi);
+            lo[gi] = f32_to_h16<F16>(sgi - h16_to_f32<F16>(hi[gi]));
         }
         xo = make_uint4(hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16), lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16));
         if (FINE ? q != (n >> 3) : (NOLUT ? q > 2 : q > 0)) xo = make_uint4(0, 0, 0, 0);
@@ -671,7 +681,7 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
         return b;
     };
     auto mfma = [&](const uint4& a, const uint4& b, const f32x4& c) -> f32x4 {
-        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+        return mfma16<F16>(a, b, c);
     };
     // lane part of a table address for table buffer 0 / its increment for buffer 1
     const uint32_t low0 = BITS == 2 ? (uint32_t)(n * 16 + (q & 1) * 8) : (uint32_t)(n * 8 + (q & 1) * 4);
@@ -696,7 +706,7 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
             }
             const int64_t col = (int64_t)t * kTile + nn;
             if (col < N) {
-                if (p.slabs == 1) p.y[(int64_t)m * N + col] = (uint16_t)f32_to_bf16(s);
+                if (p.slabs == 1) p.y[(int64_t)m * N + col] = (uint16_t)f32_to_h16<F16>(s);
                 else splitk_store(p.partial + ((int64_t)slab * M + m) * N + col, s);
             }
         }
@@ -864,7 +874,7 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
                     }
 #pragma unroll
                     for (int u = 0; u < UC; ++u)
-                        if (live[u]) p.y[dst[u]] = (uint16_t)f32_to_bf16(s[u]);
+                        if (live[u]) p.y[dst[u]] = (uint16_t)f32_to_h16<F16>(s[u]);
                 }
             };
             // few slabs: more outputs at a time instead (no repeated loads of the last slab)
@@ -938,9 +948,10 @@ StreamPlan plan_stream(int64_t M, int64_t N, int64_t K, int cus) {
     return best;
 }
 
-template <int BITS, int GW, bool AUX, bool NOLUT = false, bool REPACK = false, bool COARSE = false, bool FINE = false>
+template <int BITS, int GW, bool AUX, bool NOLUT = false, bool REPACK = false, bool COARSE = false, bool FINE = false,
+          bool F16 = false>
 static hipError_t launch_stream_t(const Params& p, int grid, hipStream_t stream) {
-    auto kern = stream::decode_stream_kernel<BITS, GW, AUX, NOLUT, REPACK, COARSE, FINE>;
+    auto kern = stream::decode_stream_kernel<BITS, GW, AUX, NOLUT, REPACK, COARSE, FINE, F16>;
 #ifdef ANY4_STAMPS
     constexpr int lds = stream::lds_bytes(BITS, FINE && AUX) + stream::kWaves * stream::kStampSteps * 4 * 8;
 #else
@@ -968,7 +979,7 @@ static hipError_t launch_stream_b(const Params& p, const StreamPlan& sp, int gri
 
 hipError_t launch_decode_stream(const uint16_t* x, const uint32_t* codes, const uint16_t* lut,
                                 const uint16_t* scale, const uint16_t* offset, int64_t M, int64_t N,
-                                int64_t K, int bits, int lr, bool repacked, const StreamPlan& sp_in, uint16_t* y,
+                                int64_t K, int bits, int lr, bool repacked, bool f16, const StreamPlan& sp_in, uint16_t* y,
                                 void* workspace, hipStream_t stream) {
     const StreamPlan& sp = sp_in;
     Params p{};
@@ -983,6 +994,24 @@ hipError_t launch_decode_stream(const uint16_t* x, const uint32_t* codes, const 
     if (const char* e = getenv("ANY4_TUNE_STOP")) p.stop = atoi(e);
 #endif
     const int grid = sp.slabs * sp.blocks_per_slab;
+    if (f16) {
+        // fp16: the table-based kernels on the plain layout with groups of 128
+        if (lut == nullptr || repacked || lr != 0) return hipErrorInvalidValue;
+#define ANY4_STREAM_H(B, GW)                                                               \
+        return sp.aux ? launch_stream_t<B, GW, true, false, false, false, false, true>(p, grid, stream)   \
+                      : launch_stream_t<B, GW, false, false, false, false, false, true>(p, grid, stream)
+#define ANY4_STREAM_HB(B)                                                                  \
+        switch (sp.gw) {                                                                   \
+            case 4: ANY4_STREAM_H(B, 4);                                                   \
+            case 2: ANY4_STREAM_H(B, 2);                                                   \
+            default: ANY4_STREAM_H(B, 1);                                                  \
+        }
+        if (bits == 4) { ANY4_STREAM_HB(4) }
+        if (bits == 3) { ANY4_STREAM_HB(3) }
+        ANY4_STREAM_HB(2)
+#undef ANY4_STREAM_HB
+#undef ANY4_STREAM_H
+    }
     if (bits == 4 && lut == nullptr) {                     // the integer grid: no table
         if (repacked || lr != 0) return hipErrorInvalidValue;
 #define ANY4_STREAM_NL(GW)                                                                 \

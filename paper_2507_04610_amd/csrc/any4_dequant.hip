@@ -1,4 +1,5 @@
 // any4_dequant: materialise w[n][k] = fma(LUT[n][code], scale[n][k/128], offset[n][k/128]) in fp32
+// (table, scale and offset stored as bf16, or as fp16 with F16)
 // (any4 paper, section 2.4.1 for the per-row table, section 2.5.2 for alpha * w_Q + beta).
 // The result is defined bit for bit: one fp32 fused multiply-add per weight.
 //
@@ -10,7 +11,7 @@
 
 namespace any4 {
 
-template <int BITS>
+template <int BITS, bool F16>
 __global__ __launch_bounds__(256) void dequant_kernel(const uint32_t* __restrict__ codes,
                                                       const uint16_t* __restrict__ lut,
                                                       const uint16_t* __restrict__ scale,
@@ -20,7 +21,7 @@ __global__ __launch_bounds__(256) void dequant_kernel(const uint32_t* __restrict
     constexpr uint32_t mask = L - 1;
     __shared__ float table[L];
     const int64_t n = blockIdx.x;
-    if (threadIdx.x < L) table[threadIdx.x] = lut ? bf16_to_f32(lut[n * L + threadIdx.x]) : (float)((int)threadIdx.x - L / 2);   // no table: the integer grid
+    if (threadIdx.x < L) table[threadIdx.x] = lut ? h16_to_f32<F16>(lut[n * L + threadIdx.x]) : (float)((int)threadIdx.x - L / 2);   // no table: the integer grid
     __syncthreads();
 
     const uint32_t* row = codes + n * row_words(K, BITS);
@@ -35,8 +36,8 @@ __global__ __launch_bounds__(256) void dequant_kernel(const uint32_t* __restrict
         if (BITS == 3 && sh > 20) window |= (uint64_t)row[word + 1] << 32;   // 12 bits straddle
         const uint32_t c4 = (uint32_t)(window >> sh);
         const int g = q >> gsh;                         // (4q) / group size
-        const float s = bf16_to_f32(scale[n * G + g]);
-        const float o = bf16_to_f32(offset[n * G + g]);
+        const float s = h16_to_f32<F16>(scale[n * G + g]);
+        const float o = h16_to_f32<F16>(offset[n * G + g]);
         float4 r;
         r.x = __builtin_fmaf(table[(c4 >> (0 * BITS)) & mask], s, o);
         r.y = __builtin_fmaf(table[(c4 >> (1 * BITS)) & mask], s, o);
@@ -47,15 +48,21 @@ __global__ __launch_bounds__(256) void dequant_kernel(const uint32_t* __restrict
 }
 
 hipError_t launch_dequant(const uint32_t* codes, const uint16_t* lut, const uint16_t* scale,
-                          const uint16_t* offset, int64_t N, int64_t K, int bits, int lr,
+                          const uint16_t* offset, int64_t N, int64_t K, int bits, int lr, bool f16,
                           float* w, hipStream_t stream) {
     if (N > 0x7FFFFFFF || K > (int64_t)1 << 28) return hipErrorInvalidValue;
     const dim3 grid((unsigned)N), block(256);
+#define ANY4_DEQUANT(B)                                                                                   \
+    do {                                                                                                  \
+        if (f16) hipLaunchKernelGGL((dequant_kernel<B, true>), grid, block, 0, stream, codes, lut, scale, offset, K, lr, w);   \
+        else hipLaunchKernelGGL((dequant_kernel<B, false>), grid, block, 0, stream, codes, lut, scale, offset, K, lr, w);      \
+    } while (0)
     switch (bits) {
-        case 4: hipLaunchKernelGGL(dequant_kernel<4>, grid, block, 0, stream, codes, lut, scale, offset, K, lr, w); break;
-        case 3: hipLaunchKernelGGL(dequant_kernel<3>, grid, block, 0, stream, codes, lut, scale, offset, K, lr, w); break;
-        default: hipLaunchKernelGGL(dequant_kernel<2>, grid, block, 0, stream, codes, lut, scale, offset, K, lr, w); break;
+        case 4: ANY4_DEQUANT(4); break;
+        case 3: ANY4_DEQUANT(3); break;
+        default: ANY4_DEQUANT(2); break;
     }
+#undef ANY4_DEQUANT
     return hipGetLastError();
 }
 

@@ -22,6 +22,25 @@ __device__ __forceinline__ uint32_t f32_to_bf16(float f) {
     return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
 }
 
+// The 16-bit storage type of tables, scales, offsets and activations: bf16, or IEEE fp16 with F16.
+// Widening is exact; narrowing rounds to nearest even.
+template <bool F16> __device__ __forceinline__ float h16_to_f32(uint32_t bits16) {
+    if constexpr (F16) return (float)__builtin_bit_cast(_Float16, (uint16_t)bits16);
+    else return bf16_to_f32(bits16);
+}
+template <bool F16> __device__ __forceinline__ float h16lo_to_f32(uint32_t pair) {
+    if constexpr (F16) return (float)__builtin_bit_cast(_Float16, (uint16_t)(pair & 0xFFFFu));
+    else return bf16lo_to_f32(pair);
+}
+template <bool F16> __device__ __forceinline__ float h16hi_to_f32(uint32_t pair) {
+    if constexpr (F16) return (float)__builtin_bit_cast(_Float16, (uint16_t)(pair >> 16));
+    else return bf16hi_to_f32(pair);
+}
+template <bool F16> __device__ __forceinline__ uint32_t f32_to_h16(float f) {
+    if constexpr (F16) return (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)f);
+    else return f32_to_bf16(f);
+}
+
 // words per packed row
 __host__ __device__ __forceinline__ int64_t row_words(int64_t K, int bits) { return K * bits / 32; }
 

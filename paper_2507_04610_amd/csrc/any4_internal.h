@@ -35,7 +35,7 @@ GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int bits);
 hipError_t launch_pack(const uint8_t* codes_u8, int64_t N, int64_t K, int bits,
                        uint32_t* codes, hipStream_t stream);
 hipError_t launch_dequant(const uint32_t* codes, const uint16_t* lut, const uint16_t* scale,
-                          const uint16_t* offset, int64_t N, int64_t K, int bits, int lr,
+                          const uint16_t* offset, int64_t N, int64_t K, int bits, int lr, bool f16,
                           float* w, hipStream_t stream);
 hipError_t launch_decode(const uint16_t* x, const uint32_t* codes, const uint16_t* lut,
                          const uint16_t* scale, const uint16_t* offset,
@@ -43,12 +43,12 @@ hipError_t launch_decode(const uint16_t* x, const uint32_t* codes, const uint16_
                          uint16_t* y, float* partial, hipStream_t stream);
 hipError_t launch_decode_stream(const uint16_t* x, const uint32_t* codes, const uint16_t* lut,
                                 const uint16_t* scale, const uint16_t* offset, int64_t M, int64_t N,
-                                int64_t K, int bits, int lr, bool repacked, const StreamPlan& sp, uint16_t* y,
+                                int64_t K, int bits, int lr, bool repacked, bool f16, const StreamPlan& sp, uint16_t* y,
                                 void* workspace, hipStream_t stream);
 hipError_t launch_reduce_slices(const float* partial, int ksplit, int64_t MN, uint16_t* y, hipStream_t stream);
 hipError_t launch_prefill(const uint16_t* x, const uint32_t* codes, const uint16_t* lut,
                           const uint16_t* scale, const uint16_t* offset,
-                          int64_t M, int64_t N, int64_t K, int bits, int lr, bool repacked, int cus,
+                          int64_t M, int64_t N, int64_t K, int bits, int lr, bool repacked, bool f16, int cus,
                           uint16_t* y, void* workspace, hipStream_t stream);
 // Tile-major re-layout of the packed codes (any4_repack).
 hipError_t launch_repack(const uint32_t* codes, int64_t N, int64_t K, int bits, uint32_t* out, hipStream_t stream);

@@ -33,6 +33,7 @@
 namespace any4 {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) u32x4* lds_u4;
@@ -52,6 +53,7 @@ __device__ __forceinline__ void lds_barrier() {                 // outstanding g
 // X[m][g] = sum of the 128 activations of group g, in fp32, stored as two bf16 (high part,
 // remainder) at xs[m][2g], xs[m][2g+1]; columns 2G .. KP-1 are zero.  16 lanes per (m, g).
 // `fine`: groups of 64 activations, 8 lanes each.
+template <bool F16>
 __global__ __launch_bounds__(256) void group_sums_kernel(const uint16_t* __restrict__ x, int64_t M,
                                                          int64_t K, int KP, int fine, uint16_t* __restrict__ xs) {
     const int lanes = fine ? 8 : 16;
@@ -61,8 +63,8 @@ __global__ __launch_bounds__(256) void group_sums_kernel(const uint16_t* __restr
     const bool live = unit < M * G;
     const int64_t u = live ? unit : 0;
     const uint4 v = reinterpret_cast<const uint4*>(x + u * (8 * lanes))[sub];    // x is [M][G][8 * lanes]
-    float s = ((bf16lo_to_f32(v.x) + bf16hi_to_f32(v.x)) + (bf16lo_to_f32(v.y) + bf16hi_to_f32(v.y))) +
-              ((bf16lo_to_f32(v.z) + bf16hi_to_f32(v.z)) + (bf16lo_to_f32(v.w) + bf16hi_to_f32(v.w)));
+    float s = ((h16lo_to_f32<F16>(v.x) + h16hi_to_f32<F16>(v.x)) + (h16lo_to_f32<F16>(v.y) + h16hi_to_f32<F16>(v.y))) +
+              ((h16lo_to_f32<F16>(v.z) + h16hi_to_f32<F16>(v.z)) + (h16lo_to_f32<F16>(v.w) + h16hi_to_f32<F16>(v.w)));
     // rotations inside rows of 16 lanes: after 1, 2, 4 a lane holds the sum of itself and the 7 lanes
     // before it (the last lane of a group of 8: its group); after 8, every lane holds the row's sum
     s += __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(s), 0x121, 0xF, 0xF, false));
@@ -72,8 +74,8 @@ __global__ __launch_bounds__(256) void group_sums_kernel(const uint16_t* __restr
     if (!live) return;
     const int64_t m = u / G, g = u % G;
     if (sub == lanes - 1) {
-        const uint32_t hi = f32_to_bf16(s);
-        const uint32_t lo = f32_to_bf16(s - bf16_to_f32(hi));
+        const uint32_t hi = f32_to_h16<F16>(s);
+        const uint32_t lo = f32_to_h16<F16>(s - h16_to_f32<F16>(hi));
         *reinterpret_cast<uint32_t*>(xs + m * KP + 2 * g) = hi | (lo << 16);
     }
     // zero padding of the row tail, done by the lanes of the row's last group
@@ -87,7 +89,8 @@ __global__ __launch_bounds__(256) void group_sums_kernel(const uint16_t* __restr
 // the bf16 value sits in the low half of the dword).
 // FINE: groups of 64 weights - every K step is a group of its own (scale index 2g, 2g + 1 for the two
 // steps of chunk g; the offset phase runs over 64-weight groups).  Otherwise groups of 128 << lr.
-template <int BITS, bool FINE>
+// F16: activations, table, scales, offsets and output are fp16 instead of bf16.
+template <int BITS, bool FINE, bool F16>
 __global__ __launch_bounds__(PTHREADS, 1) void prefill_kernel(
     const uint16_t* __restrict__ x, const uint32_t* __restrict__ codes,
     const uint16_t* __restrict__ lut, const uint16_t* __restrict__ scale,
@@ -95,6 +98,12 @@ __global__ __launch_bounds__(PTHREADS, 1) void prefill_kernel(
     int64_t M, int64_t N, int64_t K, int lr, int repacked, int gm, int tail_first, int tail_s,
     unsigned long long* __restrict__ counters, float* __restrict__ partial, uint16_t* __restrict__ y) {
     constexpr int L = 1 << BITS;
+    static_assert(!(F16 && FINE), "fp16 comes with groups of 128 and more");
+    using op16x8 = std::conditional_t<F16, f16x8, bf16x8>;
+    auto mma = [](const op16x8& a, const op16x8& b, const f32x16& c) -> f32x16 {
+        if constexpr (F16) return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+        else return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+    };
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     uint32_t* table = reinterpret_cast<uint32_t*>(smem + kTableOff);      // [PBN / 8][L][32]
 
@@ -195,14 +204,14 @@ __global__ __launch_bounds__(PTHREADS, 1) void prefill_kernel(
     auto step = [&](auto buf_, auto first_, auto fold_, uint32_t (&q)[2], int tile_q, int tile_x, uint32_t sraw0, uint32_t sraw1) {
         constexpr int BUF = decltype(buf_)::value;
         constexpr bool FIRST = decltype(first_)::value, FOLD = decltype(fold_)::value;
-        bf16x8 a[2][2], b[2][2];
+        op16x8 a[2][2], b[2][2];
         uint32_t lk[2][8], wpk[4];
         uint32_t lo, hi;
         auto read_ops = [&](int set, int kk) {
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
-                a[set][i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<lds_u4>(ard + BUF * kXBuf + i * (32 * PLD * 2) + kk * 32));
-                b[set][i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<lds_u4>(brd + BUF * kWBuf + i * (32 * PLD * 2) + kk * 32));
+                a[set][i] = __builtin_bit_cast(op16x8, *reinterpret_cast<lds_u4>(ard + BUF * kXBuf + i * (32 * PLD * 2) + kk * 32));
+                b[set][i] = __builtin_bit_cast(op16x8, *reinterpret_cast<lds_u4>(brd + BUF * kWBuf + i * (32 * PLD * 2) + kk * 32));
             }
         };
         auto w_issue = [&](int c, int h) {                      // four of the eight lookups of chunk c
@@ -239,7 +248,7 @@ __global__ __launch_bounds__(PTHREADS, 1) void prefill_kernel(
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 const int i = t >> 1, j = t & 1;
-                part[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cur][i], b[cur][j], (FIRST && kk == 0) ? zero : part[i][j], 0, 0, 0);
+                part[i][j] = mma(a[cur][i], b[cur][j], (FIRST && kk == 0) ? zero : part[i][j]);
                 if (kk == 0) {
                     if (t < 2) w_finish(0, t);
                     else w_issue(1, t - 2);
@@ -252,7 +261,7 @@ __global__ __launch_bounds__(PTHREADS, 1) void prefill_kernel(
                 } else if (FOLD) {
                     // the scales were fetched two K steps ago; widening them here, not earlier,
                     // keeps the wait for that fetch away from the start of the group
-                    if (t == 1) { s0 = bf16_to_f32(sraw0); s1 = bf16_to_f32(sraw1); }
+                    if (t == 1) { s0 = h16_to_f32<F16>(sraw0); s1 = h16_to_f32<F16>(sraw1); }
                     if (t >= 2) fold(t - 2);
                 }
                 ANY4_SB();
@@ -264,17 +273,17 @@ __global__ __launch_bounds__(PTHREADS, 1) void prefill_kernel(
     auto mma_plain = [&]() {
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
-            bf16x8 a[2], b[2];
+            op16x8 a[2], b[2];
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
-                a[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<lds_u4>(ard + i * (32 * PLD * 2) + kk * 32));
-                b[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<lds_u4>(brd + i * (32 * PLD * 2) + kk * 32));
+                a[i] = __builtin_bit_cast(op16x8, *reinterpret_cast<lds_u4>(ard + i * (32 * PLD * 2) + kk * 32));
+                b[i] = __builtin_bit_cast(op16x8, *reinterpret_cast<lds_u4>(brd + i * (32 * PLD * 2) + kk * 32));
             }
 #pragma unroll
             for (int i = 0; i < 2; ++i)
 #pragma unroll
                 for (int j = 0; j < 2; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = mma(a[i], b[j], acc[i][j]);
         }
     };
     using B0 = std::integral_constant<int, 0>;
@@ -296,8 +305,8 @@ __global__ __launch_bounds__(PTHREADS, 1) void prefill_kernel(
             if (lut) v = *reinterpret_cast<const uint2*>(lut + min(n0 + row, N - 1) * L + pc * 4);
             else {                                             // no table: the integer grid, entries pc * 4 .. + 3
                 const int c0 = pc * 4 - L / 2;
-                v.x = f32_to_bf16((float)c0) | (f32_to_bf16((float)(c0 + 1)) << 16);
-                v.y = f32_to_bf16((float)(c0 + 2)) | (f32_to_bf16((float)(c0 + 3)) << 16);
+                v.x = f32_to_h16<F16>((float)c0) | (f32_to_h16<F16>((float)(c0 + 1)) << 16);
+                v.y = f32_to_h16<F16>((float)(c0 + 2)) | (f32_to_h16<F16>((float)(c0 + 3)) << 16);
             }
             uint32_t* dst = table + (row >> 3) * (32 << BITS) + (pc * 4) * 32 + (row & 7) * 4;
             const uint32_t e0 = v.x & 0xFFFFu, e1 = v.x >> 16, e2 = v.y & 0xFFFFu, e3 = v.y >> 16;
@@ -382,7 +391,7 @@ __global__ __launch_bounds__(PTHREADS, 1) void prefill_kernel(
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int64_t m = m0 + wm * 64 + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
-            if (m < M && n < N) y[m * N + n] = (uint16_t)f32_to_bf16(r[v]);
+            if (m < M && n < N) y[m * N + n] = (uint16_t)f32_to_h16<F16>(r[v]);
         }
     };
     if (slice < 0) {
@@ -475,11 +484,11 @@ size_t prefill_workspace_bytes(int64_t M, int64_t N, int64_t K, int cus) {
 
 hipError_t launch_prefill(const uint16_t* x, const uint32_t* codes, const uint16_t* lut,
                           const uint16_t* scale, const uint16_t* offset,
-                          int64_t M, int64_t N, int64_t K, int bits, int lr, bool repacked, int cus,
+                          int64_t M, int64_t N, int64_t K, int bits, int lr, bool repacked, bool f16, int cus,
                           uint16_t* y, void* workspace, hipStream_t stream) {
     const PrefillPlan pp = plan_prefill(M, N, K, cus);
     const bool fine = lr < 0;
-    if (lr < -1) return hipErrorInvalidValue;
+    if (lr < -1 || (f16 && fine)) return hipErrorInvalidValue;
     const int64_t sblocks = (M * (K / 8) + 255) / 256;         // one lane per 8 activations
     const int64_t nblocks = pp.tiles - pp.tail_tiles + pp.tail_tiles * pp.tail_s;
     if (pp.gm > 0x7FFFFFFF || nblocks > 0x7FFFFFFF || sblocks > 0x7FFFFFFF || K / kGroup > 0x1FFFFFFF) return hipErrorInvalidValue;
@@ -487,20 +496,26 @@ hipError_t launch_prefill(const uint16_t* x, const uint32_t* codes, const uint16
     uint16_t* xsums = static_cast<uint16_t*>(workspace);
     unsigned long long* counters = reinterpret_cast<unsigned long long*>(static_cast<char*>(workspace) + pp.xsums_bytes);
     float* partial = reinterpret_cast<float*>(static_cast<char*>(workspace) + pp.xsums_bytes + pp.counter_bytes);
-    hipLaunchKernelGGL(group_sums_kernel, dim3((unsigned)sblocks), dim3(256), 0, stream, x, M, K, KP, fine ? 1 : 0, xsums);
+    if (f16) hipLaunchKernelGGL(group_sums_kernel<true>, dim3((unsigned)sblocks), dim3(256), 0, stream, x, M, K, KP, 0, xsums);
+    else hipLaunchKernelGGL(group_sums_kernel<false>, dim3((unsigned)sblocks), dim3(256), 0, stream, x, M, K, KP, fine ? 1 : 0, xsums);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const dim3 grid((unsigned)nblocks), block(PTHREADS);
     const int gm = (int)pp.gm, tail_first = (int)(pp.tiles - pp.tail_tiles), tail_s = pp.tail_s;
-#define ANY4_PREFILL_F(B, F)                                                                                      \
+#define ANY4_PREFILL_F(B, F, H)                                                                                   \
     do {                                                                                                          \
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(prefill_kernel<B, F>),                              \
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(prefill_kernel<B, F, H>),                           \
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)prefill_lds_bytes(B));           \
         if (e != hipSuccess) return e;                                                                            \
-        hipLaunchKernelGGL((prefill_kernel<B, F>), grid, block, prefill_lds_bytes(B), stream, x, codes, lut, scale, \
+        hipLaunchKernelGGL((prefill_kernel<B, F, H>), grid, block, prefill_lds_bytes(B), stream, x, codes, lut, scale, \
                            offset, xsums, KP, M, N, K, F ? 0 : lr, repacked ? 1 : 0, gm, tail_first, tail_s, counters, partial, y); \
     } while (0)
-#define ANY4_PREFILL(B) do { if (fine) ANY4_PREFILL_F(B, true); else ANY4_PREFILL_F(B, false); } while (0)
+#define ANY4_PREFILL(B)                                                                                           \
+    do {                                                                                                          \
+        if (f16) ANY4_PREFILL_F(B, false, true);                                                                  \
+        else if (fine) ANY4_PREFILL_F(B, true, false);                                                            \
+        else ANY4_PREFILL_F(B, false, false);                                                                     \
+    } while (0)
     switch (bits) {
         case 4: ANY4_PREFILL(4); break;
         case 3: ANY4_PREFILL(3); break;

@@ -385,6 +385,58 @@ def test_grouped_rejects_other_group_sizes(any4):
         any4.any4_dequant(codes, dev_bf16(cs.lut), dev_bf16(cs.scale), dev_bf16(cs.offset), 640, 4, group=256)
 
 
+# ------------------------------------------------------------------------------ fp16 storage
+def dev_f16(a_u16):
+    return torch.from_numpy(np.ascontiguousarray(a_u16).view(np.int16)).cuda().view(torch.float16)
+
+
+@pytest.mark.parametrize("bits", (4, 3, 2))
+@pytest.mark.parametrize("N,K", [(1, 128), (130, 640), (17, 14336)])
+def test_dequant_f16_bit_exact(any4, oracle, bits, N, K):
+    cs = inputs.make_case(1, N, K, bits, seed=inputs.case_seed(21, bits, N % 7), f16=True)
+    packed = oracle.pack(cs.codes_u8, bits)
+    w_ref = oracle.dequant(packed, cs.lut, cs.scale, cs.offset, K, bits, f16=True)
+    w = any4.any4_dequant(dev_codes(packed), dev_f16(cs.lut), dev_f16(cs.scale), dev_f16(cs.offset), K, bits)
+    torch.cuda.synchronize()
+    assert np.array_equal(w.cpu().numpy().view(np.uint32), w_ref.view(np.uint32))
+
+
+@pytest.mark.parametrize("bits", (4, 3, 2))
+@pytest.mark.parametrize("M,N,K", [(1, 16, 128), (1, 333, 4224), (2, 40, 28672), (3, 17, 384), (5, 48, 14336), (8, 700, 640),
+                                   (16, 100, 4480), (1, 2049, 256), (17, 128, 128), (40, 512, 4096), (100, 200, 256),
+                                   (129, 130, 640), (300, 64, 2048), (260, 300, 8192)])
+def test_gemm_f16(any4, oracle, bits, M, N, K):
+    """fp16 activations, table, scales, offsets and output (the f16 matrix instructions): small M
+    with one and several K slabs, shared small inputs on and off, a few dozen rows, large M with
+    whole tiles and K slices.  Bar: 1e-2 * rms + half an fp16 unit of output rounding (2^-11 |y|)."""
+    cs = inputs.make_case(M, N, K, bits, seed=inputs.case_seed(22, bits, M + N), f16=True)
+    packed = oracle.pack(cs.codes_u8, bits)
+    y64 = oracle.gemm(cs.x, packed, cs.lut, cs.scale, cs.offset, K, bits, threads=8, f16=True)
+    y = any4.any4_gemm(dev_f16(cs.x), dev_codes(packed), dev_f16(cs.lut), dev_f16(cs.scale), dev_f16(cs.offset), bits)
+    torch.cuda.synchronize()
+    assert y.dtype == torch.float16 and y.shape == (M, N)
+    got = y.cpu().numpy().astype(np.float64)
+    rms = oracle.rms(y64)
+    tol = 1e-2 * rms + np.abs(y64) * 2.0 ** -11
+    err = np.abs(got - y64)
+    worst = np.unravel_index(np.argmax(err - tol), err.shape)
+    assert np.all(err <= tol), ("f16", M, N, K, bits, worst, float(err[worst]), float(tol[worst]), rms)
+
+
+def test_f16_needs_a_table_groups_of_128_and_one_dtype(any4):
+    cs = inputs.make_case(1, 16, 256, 4, 3, f16=True)
+    codes = any4.any4_pack(torch.from_numpy(cs.codes_u8).cuda(), 4)
+    x, lut, sc, of = dev_f16(cs.x), dev_f16(cs.lut), dev_f16(cs.scale), dev_f16(cs.offset)
+    with pytest.raises(any4.Any4Error):
+        any4.any4_gemm(x, codes, None, sc, of, 4)
+    with pytest.raises(any4.Any4Error):
+        any4.any4_gemm(x, codes, lut, sc[:, ::2].contiguous(), of[:, ::2].contiguous(), 4, group=256)
+    with pytest.raises(any4.Any4Error):
+        any4.any4_gemm(x, codes, lut.view(torch.bfloat16), sc, of, 4)             # mixed types
+    with pytest.raises(any4.Any4Error):
+        any4.any4_gemm_repacked(x, any4.any4_repack(codes, 4), lut, sc, of, 4)
+
+
 # ------------------------------------------------------------------------------ tile-major re-layout
 @pytest.mark.parametrize("bits", (4, 3, 2))
 @pytest.mark.parametrize("N,K", [(16, 128), (21, 256), (1, 128), (257, 1152), (64, 4096), (5, 14336)])
