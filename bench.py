@@ -429,7 +429,13 @@ def main():
                     [(lambda p_=p_, c_=c_: any4.any4_gemm(p_["x"], p_["codes"], p_["lut"], c_[0], c_[1], bits, out=p_["y"],
                                                           workspace=p_["ws"], group=grp)) for p_, c_ in zip(rot, coarse)])
                 del coarse
-            del rot, shared
+            # fp16 in place of bf16 (section 2.4.1 names both): the same values converted
+            half = [{k_: p_[k_].to(torch.float16) for k_ in ("x", "lut", "scale", "offset")} for p_ in rot]
+            yh = [torch.empty_like(p_["y"], dtype=torch.float16) for p_ in rot]
+            fm[g["name"]]["any4_f16_us"] = graph_us(
+                [(lambda p_=p_, h_=h_, y_=y_: any4.any4_gemm(h_["x"], p_["codes"], h_["lut"], h_["scale"], h_["offset"], bits,
+                                                             out=y_, workspace=p_["ws"])) for p_, h_, y_ in zip(rot, half, yh)])
+            del rot, shared, half, yh
             torch.cuda.empty_cache()
         extras["formats_llama3_8b_M1"] = fm
         layers = [layers_keep]
