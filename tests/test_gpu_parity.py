@@ -516,6 +516,44 @@ def test_llama3_8b_decode_and_prefill_shapes(any4, oracle, name):
     sampled_rows_check(any4, oracle, name, N, K, 4, (1, 8, 2048), seed=inputs.case_seed(20, i))
 
 
+@pytest.mark.parametrize("variant", ("group64", "group1024", "f16"))
+@pytest.mark.parametrize("name", list(inputs.LLAMA3_8B_SHAPES))
+def test_llama3_8b_shapes_other_groups_and_fp16(any4, oracle, name, variant):
+    """The full 8B linears at M = 1, 8 and 2048 with groups of 64 / 1024 weights and with fp16 storage:
+    sampled output columns against the oracle."""
+    N, K = inputs.LLAMA3_8B_SHAPES[name]
+    i = list(inputs.LLAMA3_8B_SHAPES).index(name)
+    seed = inputs.case_seed(60, i, len(variant))
+    f16 = variant == "f16"
+    group = {"group64": 64, "group1024": 1024, "f16": 128}[variant]
+    if K % group:
+        pytest.skip("the group must divide K")
+    Ms = (1, 8, 2048)
+    cs = inputs.make_case(max(Ms), N, K, 4, seed, f16=f16)
+    if group == 64:
+        other = inputs.make_case(1, N, K, 4, seed + 1000)
+        sc = np.ascontiguousarray(np.stack([cs.scale, other.scale], axis=2).reshape(N, -1))
+        of = np.ascontiguousarray(np.stack([cs.offset, other.offset], axis=2).reshape(N, -1))
+    else:
+        sc, of = np.ascontiguousarray(cs.scale[:, ::group // 128]), np.ascontiguousarray(cs.offset[:, ::group // 128])
+    dev = dev_f16 if f16 else dev_bf16
+    codes_dev = any4.any4_pack(torch.from_numpy(cs.codes_u8).cuda(), 4)
+    lut_d, sc_d, of_d = dev(cs.lut), dev(sc), dev(of)
+    rng = np.random.default_rng(seed + 1)
+    rows = np.unique(np.concatenate([[0, 1, N - 2, N - 1], rng.integers(0, N, SAMPLE_ROWS)]))
+    idx = torch.from_numpy(rows).cuda()
+    packed_rows = oracle.pack(cs.codes_u8[rows], 4)
+    for M in Ms:
+        x = cs.x[:M]
+        y64 = oracle.gemm(x, packed_rows, cs.lut[rows], sc[rows], of[rows], K, 4, threads=8, group=group, f16=f16)
+        y = any4.any4_gemm(dev(x), codes_dev, lut_d, sc_d, of_d, 4, group=group)
+        torch.cuda.synchronize()
+        got = y[:, idx].float().cpu().numpy().astype(np.float64)
+        rms = oracle.rms(y64)
+        tol = 1e-2 * rms + np.abs(y64) * (2.0 ** -11 if f16 else 2.0 ** -8)
+        assert np.all(np.abs(got - y64) <= tol), (name, variant, M, float(np.abs(got - y64).max()), rms)
+
+
 @pytest.mark.parametrize("name", list(inputs.LLAMA3_70B_SHAPES))
 def test_llama3_70b_batch_sweep(any4, oracle, name):
     """Config 3: M in {1, 2, 4, 8, 16} on the 70B linears."""
