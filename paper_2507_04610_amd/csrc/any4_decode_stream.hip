@@ -312,9 +312,12 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
             *reinterpret_cast<uint2*>(dst + 64) = make_uint2(v1, v1);
         } else {
             // entry e of row n at dword e * 64 + par * 16384 + n * 4, both copies (16 bytes)
-            auto val = [&](int c) -> uint32_t { return ((c & 2) ? l.a[1] : l.a[0]) >> (16 * (c & 1)) & 0xFFFFu; };
+            // (copies first: a choice between l.a[0] and l.a[1] by a lane-dependent index is otherwise
+            // compiled as an indexed load from a copy of the struct in scratch memory, once per tile)
+            const uint32_t a0 = l.a[0], a1 = l.a[1];
+            auto val = [&](int c) -> uint32_t { return ((c & 2) ? a1 : a0) >> (16 * (c & 1)) & 0xFFFFu; };
             auto valv = [&](uint32_t c) -> uint32_t {            // lane-dependent index
-                const uint32_t d = (c & 2u) ? l.a[1] : l.a[0];
+                const uint32_t d = (c & 2u) ? a1 : a0;
                 return (c & 1u) ? (d >> 16) : (d & 0xFFFFu);
             };
             const uint32_t d1 = valv(((uint32_t)(w & 1) << 1) | (uint32_t)(q >> 1)) | (valv((uint32_t)(w >> 1)) << 16);
@@ -332,19 +335,21 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
     //      row's table by lanes j < 2 (any4, 16 bytes each) or j = 0 (any3: 16 bytes, any2: 8)) and
     //      written to an LDS slot two tiles later.  Table rows keep a 32-byte stride in the slot.
     uint2 axs[2], axo[2];
-    uint4 fxs[2], fxo[2];                                  // FINE: twice the entries
+    // FINE: twice the entries.  (Plain vector variables, not arrays of HIP's uint4: those the compiler
+    // kept in scratch memory across the tile loop, with a store - and a full wait - right after each load.)
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    u32x4 fxs0 = {0, 0, 0, 0}, fxs1 = {0, 0, 0, 0}, fxo0 = {0, 0, 0, 0}, fxo1 = {0, 0, 0, 0};
     uint4 axl;
     auto aux_load = [&](int t) {
         if constexpr (FINE) {
             // two entries per chunk of 128: lane (n, j) loads those of chunks 4j .. 4j+3 and 16 + 4j .. + 3
             const int64_t tile_off = (int64_t)t * (kTile * 2) * GS + gs0 * 4;
             const uint32_t vs = t == last_tile ? vs_last : vs_norm;
-#pragma unroll
-            for (int c = 0; c < 2; ++c) {
-                const uint32_t go = (uint32_t)min((c * 4 + q) * 4, max(sg, 4) - 4) * 4u;
-                fxs[c] = *reinterpret_cast<const uint4*>(scale_b + tile_off + vs + go);
-                fxo[c] = *reinterpret_cast<const uint4*>(offset_b + tile_off + vs + go);
-            }
+            const uint32_t go0 = (uint32_t)min(q * 4, max(sg, 4) - 4) * 4u, go1 = (uint32_t)min((4 + q) * 4, max(sg, 4) - 4) * 4u;
+            fxs0 = *reinterpret_cast<const u32x4*>(scale_b + tile_off + vs + go0);
+            fxo0 = *reinterpret_cast<const u32x4*>(offset_b + tile_off + vs + go0);
+            fxs1 = *reinterpret_cast<const u32x4*>(scale_b + tile_off + vs + go1);
+            fxo1 = *reinterpret_cast<const u32x4*>(offset_b + tile_off + vs + go1);
         } else if constexpr (!COARSE) {
             // lanes past the slab's groups repeat its last four: the loads are unconditional
             const int64_t tile_off = (int64_t)t * (kTile * 2) * G + gs0 * 2;
@@ -383,21 +388,25 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
     auto aux_write = [&](int slot) {
         unsigned char* s = aux + slot * kAuxSlot;
 #pragma unroll
-        for (int c = 0; c < 2; ++c)
-            if ((c * 4 + q) * 4 < sg) {
-                if constexpr (FINE) {
-                    *reinterpret_cast<uint4*>(s + kAuxScale + n * kAuxRow + (c * 4 + q) * 16) = fxs[c];
-                    *reinterpret_cast<uint4*>(s + kAuxOffset + n * kAuxRow + (c * 4 + q) * 16) = fxo[c];
-                    continue;
+        for (int c = 0; c < 2; ++c) {
+            const bool in_slab = (c * 4 + q) * 4 < sg;
+            if constexpr (FINE) {
+                if (in_slab) {
+                    *reinterpret_cast<u32x4*>(s + kAuxScale + n * kAuxRow + (c * 4 + q) * 16) = c ? fxs1 : fxs0;
+                    *reinterpret_cast<u32x4*>(s + kAuxOffset + n * kAuxRow + (c * 4 + q) * 16) = c ? fxo1 : fxo0;
                 }
+            } else {
                 uint2 sv = axs[c], ov = axo[c];
                 if constexpr (COARSE) {
                     sv = make_uint2(sv.x | (sv.x << 16), sv.y | (sv.y << 16));
                     ov = make_uint2(ov.x | (ov.x << 16), ov.y | (ov.y << 16));
                 }
-                *reinterpret_cast<uint2*>(s + kAuxScale + n * kAuxRow + (c * 4 + q) * 8) = sv;
-                *reinterpret_cast<uint2*>(s + kAuxOffset + n * kAuxRow + (c * 4 + q) * 8) = ov;
+                if (in_slab) {
+                    *reinterpret_cast<uint2*>(s + kAuxScale + n * kAuxRow + (c * 4 + q) * 8) = sv;
+                    *reinterpret_cast<uint2*>(s + kAuxOffset + n * kAuxRow + (c * 4 + q) * 8) = ov;
+                }
             }
+        }
         if constexpr (NOLUT) { }
         else if constexpr (BITS == 4) { if (q < 2) *reinterpret_cast<uint4*>(s + kAuxLut + n * 32 + q * 16) = axl; }
         else if constexpr (BITS == 3) { if (q < 1) *reinterpret_cast<uint4*>(s + kAuxLut + n * 32) = axl; }
