@@ -22,7 +22,8 @@
 
 namespace any4 {
 
-constexpr int QT = 256;                 // threads per block (4 wavefronts)
+constexpr int QT = 256;                 // threads per block (4 wavefronts; several blocks share a compute unit:
+                                        // blocks of 512 or 1024 threads measured 1.2 - 2.2x slower)
 constexpr int QW = QT / kWave;
 
 __device__ __forceinline__ double shfl_xor_f64(double v, int mask) {
@@ -171,6 +172,7 @@ __global__ __launch_bounds__(QT) void quantize_kernel(
 #pragma unroll
         for (int p = 0; p < L; ++p) { num[p] = 0.0; den[p] = 0.0; }
         int changed = 0;
+#pragma unroll 2                                               // two independent chains of compare / select: 5 % faster
         for (int j = tid; j < K; j += QT) {
             const double x = (double)ws[j];
             int best = 0;
