@@ -187,10 +187,14 @@ __global__ __launch_bounds__(QT) void quantize_kernel(
             codes[j] = (unsigned char)best;
             const double s = (double)sample_weight(j);
             const double sx = s * x;
+            // num[best] += sx, den[best] += s with the accumulators in registers: one fused multiply-add
+            // per accumulator with a factor of exactly 1 or 0 (fma(v, 1, a) = a + v rounded once;
+            // fma(v, 0, a) = a), cheaper than selecting v or 0 and adding
 #pragma unroll
             for (int p = 0; p < L; ++p) {
-                num[p] += (best == p) ? sx : 0.0;
-                den[p] += (best == p) ? s : 0.0;
+                const double one = __hiloint2double(best == p ? 0x3FF00000 : 0, 0);
+                num[p] = __builtin_fma(sx, one, num[p]);
+                den[p] = __builtin_fma(s, one, den[p]);
             }
         }
         changed = __syncthreads_or(changed);
