@@ -504,7 +504,7 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
     // contiguous kilobyte per instruction) and re-distributes them to the operand layout through
     // LDS, instead of 4 * GW loads per lane that each pick 16-byte pieces out of 16 rows.  One or
     // two rows go through the partial-sum buffer (idle until the first tile; every wavefront has a
-    // slice of its own, no barrier).  More rows are fetched 8 or 16 at a time (rows past M repeat
+    // slice of its own, no barrier).  More rows are fetched 4, 8 or 16 at a time (rows past M repeat
     // row M - 1 so that the loads are unconditional) and go, kStageRows at a pass, through the table
     // buffers, which are idle until the first table is built - after a barrier in that case.
     constexpr int kStageRows = BITS == 4 ? 8 : (BITS == 2 ? 16 : 4);
@@ -531,7 +531,8 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
                 xraw[m] = has ? v : make_uint4(0, 0, 0, 0);
             }
         };
-        if (M <= 8) fetch_rows(std::integral_constant<int, 8>{});
+        if (M <= 4) fetch_rows(std::integral_constant<int, 4>{});
+        else if (M <= 8) fetch_rows(std::integral_constant<int, 8>{});
         else fetch_rows(std::integral_constant<int, kTile>{});
     }
     LutSrc lut0;
