@@ -67,3 +67,33 @@ def test_random_shapes_and_variants(oracle, sweep_seed):
         tol = 1e-2 * oracle.rms(y64) + np.abs(y64) * (2.0 ** -11 if f16 else 2.0 ** -8)
         err = np.abs(got - y64)
         assert np.all(err <= tol), (what, float((err - tol).max()))
+
+
+def test_random_dequant_pack_repack(oracle):
+    """bit-exact legs on random shapes: pack, re-layout, dequant with every group size and both
+    16-bit types"""
+    import paper_2507_04610_amd as any4
+    any4.load_library()
+    rng = np.random.default_rng(9)
+    for it in range(60):
+        bits = int(rng.choice([4, 3, 2]))
+        K = 128 * int(rng.choice([1, 2, 3, 5, 8, 16, 33, 112]))
+        N = int(rng.choice([1, 7, 16, 17, 130, 257]))
+        group = int(rng.choice([64, 128, 256, 512, 1024]))
+        f16 = bool(rng.integers(2)) and group == 128
+        if K % group:
+            group = 128
+        seed = int(rng.integers(1 << 30))
+        cs = inputs.make_case(1, N, K, bits, seed, f16=f16)
+        store = inputs.f32_to_f16_bits if f16 else inputs.f32_to_bf16_bits
+        sc = store(rng.uniform(0.005, 0.02, size=(N, K // group)).astype(np.float32))
+        of = store((rng.standard_normal((N, K // group)) * 0.002).astype(np.float32))
+        print((it, bits, N, K, group, f16, seed), flush=True)
+        packed = oracle.pack(cs.codes_u8, bits)
+        codes = any4.any4_pack(torch.from_numpy(cs.codes_u8).cuda(), bits)
+        assert np.array_equal(codes.cpu().numpy().view(np.uint32), packed)
+        assert np.array_equal(any4.any4_repack(codes, bits).cpu().numpy().view(np.uint32), oracle.repack(packed, K, bits))
+        w = any4.any4_dequant(codes, dev16(cs.lut, f16), dev16(sc, f16), dev16(of, f16), K, bits, group=group)
+        torch.cuda.synchronize()
+        w_ref = oracle.dequant(packed, cs.lut, sc, of, K, bits, group=group, f16=f16)
+        assert np.array_equal(w.cpu().numpy().view(np.uint32), w_ref.view(np.uint32))
