@@ -739,6 +739,14 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
         auto lookups = [&](int gi, uint4 (&b)[4]) {
             const Quarter c = cw[B][gi];
             b[0] = lookup(c, 0, low); b[1] = lookup(c, 1, low); b[2] = lookup(c, 2, low); b[3] = lookup(c, 3, low);
+            if constexpr (NOLUT) {
+                // The table-free operands are plain arithmetic on the code words, which the compiler would
+                // rather redo next to the matrix instructions: the code words then outlive the refill,
+                // the refill lands in other registers and every round of the tile loop ends with copies
+                // behind a wait for ALL outstanding loads.  Pin the operands here instead.
+#pragma unroll
+                for (int j = 0; j < 4; ++j) asm volatile("" : "+v"(b[j].x), "+v"(b[j].y), "+v"(b[j].z), "+v"(b[j].w));
+            }
             if constexpr (REFILL) load_codes(cw[B][gi], tn, gi);
         };
         lookups(0, bq[0]);
