@@ -341,11 +341,18 @@ __global__ __launch_bounds__(PTHREADS, 1) void prefill_kernel(
     //      writes freed the registers), codes from set (s + 1) % 2, which it then refills with the
     //      codes of step s + 3.  The last step stages a repeat of step T - 1 into a buffer that is
     //      not read again.
+    // FINE: both scales of a chunk in one aligned 4-byte load per column, fetched one chunk ahead (the
+    // first fold comes three quarters of a K step after the top of the iteration: a load issued
+    // there would be waited for together with everything issued since)
+    uint32_t pn0 = 0, pn1 = 0;
+    if constexpr (FINE) { pn0 = reinterpret_cast<const uint32_t*>(scol[0])[g_lo]; pn1 = reinterpret_cast<const uint32_t*>(scol[1])[g_lo]; }
     for (int g = g_lo; g < g_hi; ++g) {
         const int s = 2 * g;
         if constexpr (FINE) {
-            // both scales of the chunk in one aligned 4-byte load per column
-            const uint32_t p0 = reinterpret_cast<const uint32_t*>(scol[0])[g], p1 = reinterpret_cast<const uint32_t*>(scol[1])[g];
+            const uint32_t p0 = pn0, p1 = pn1;
+            const int gn = min(g + 1, g_hi - 1);
+            pn0 = reinterpret_cast<const uint32_t*>(scol[0])[gn];
+            pn1 = reinterpret_cast<const uint32_t*>(scol[1])[gn];
             step(B0{}, Yes{}, Yes{}, q1, min(s + 3, T - 1), min(s + 2, T - 1), p0 & 0xFFFFu, p1 & 0xFFFFu);
             lds_barrier();
             step(B1{}, Yes{}, Yes{}, q0, min(s + 4, T - 1), min(s + 3, T - 1), p0 >> 16, p1 >> 16);
