@@ -66,6 +66,11 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     any4.load_library()                      # raises if libany4.so was not built
+    import ctypes
+    benchlib = ctypes.CDLL(os.path.join(ROOT, "paper_2507_04610_amd", "bench_support", "libany4_bench.so"))
+    benchlib.bench_stream_read.restype = ctypes.c_int
+    benchlib.bench_stream_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_uint32, ctypes.c_void_p,
+                                           ctypes.c_void_p]
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
     bits = 4
@@ -85,6 +90,12 @@ def main():
             })
             del t["codes_u8"]
         return layer
+
+    def stream_read(buf, sink, magic=0x5EED1234):
+        """measurement helper (paper_2507_04610_amd/bench_support): read `buf` once on the current stream"""
+        rc = benchlib.bench_stream_read(buf.data_ptr(), buf.numel() * buf.element_size(), magic, sink.data_ptr(),
+                                        torch.cuda.current_stream().cuda_stream)
+        assert rc == 0, "bench_stream_read refused its arguments"
 
     def launch(g):
         any4.any4_gemm(g["x"], g["codes"], g["lut"], g["scale"], g["offset"], g.get("bits", bits), out=g["y"],
@@ -193,13 +204,13 @@ def main():
         # bytes) and do no arithmetic: same rotation over layers, same graph replay, a plain read kernel
         sink = torch.zeros(4, dtype=torch.int32, device=dev)
         for g in layers[0]:
-            any4.any4_stream_read(g["codes"], sink)
+            stream_read(g["codes"], sink)
         torch.cuda.synchronize()
         rgraph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(rgraph):
             for s_ in range(args.steps):
                 for g in layers[s_ % args.layers]:
-                    any4.any4_stream_read(g["codes"], sink)
+                    stream_read(g["codes"], sink)
         rgraph.replay()
         torch.cuda.synchronize()
         r0, r1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -210,11 +221,11 @@ def main():
         read_ms = r0.elapsed_time(r1) / args.steps
         code_bytes = sum(g["codes"].numel() * 4 for g in layers[0])
         bigbuf = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
-        any4.any4_stream_read(bigbuf, sink)
+        stream_read(bigbuf, sink)
         torch.cuda.synchronize()
         b0, b1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         b0.record()
-        any4.any4_stream_read(bigbuf, sink)
+        stream_read(bigbuf, sink)
         b1.record()
         torch.cuda.synchronize()
         extras["read_only_launches"] = {

@@ -16,12 +16,19 @@
  *   - bf16 values travel as uint16_t bit patterns.
  *   - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the default
  *     stream) and the call returns without waiting for it.
- *   - Return value: ANY4_OK (0) or a negative error code.  On error nothing was
- *     launched and no output byte was written.  No exception or abort crosses the ABI.
+ *   - Return value: ANY4_OK (0) or a negative error code.  Every argument check and every
+ *     device-independent refusal happens before the first launch: on any error other than
+ *     ANY4_ERR_HIP nothing was launched and no output byte was written.  ANY4_ERR_HIP means the
+ *     HIP runtime refused a launch; calls that are served by several launches (any4_gemm with
+ *     16 < M <= 128 or with groups of 64 and 8 < M <= 16, and the matrix-core path, whose
+ *     group-sum pre-pass precedes the GEMM kernel) may then have written part of y or of the
+ *     workspace: their contents are unspecified.  No exception or abort crosses the ABI.
  *   - K must be a positive multiple of 128 (the group size); M, N >= 1; bits is 4, 3
  *     or 2.  Every pointer must be 16-byte aligned.
- *   - The library holds no mutable global state; calls on different streams may run
- *     concurrently as long as their outputs and workspaces do not overlap.
+ *   - The library keeps no state between calls that affects results: the only process-wide data
+ *     are one-time, per-device set-up flags (the raised LDS limit of a kernel).  Calls on
+ *     different streams may run concurrently as long as their outputs and workspaces do not
+ *     overlap; two calls that share a workspace must not overlap in time.
  *
  * Packed code layout (codes[N][K*bits/32], uint32 words, per row, along K):
  *   bits = 4:  8 codes per word, code k in bits [4(k%8), 4(k%8)+4) of word k/8
@@ -91,7 +98,11 @@ int any4_dequant(const uint32_t* codes, const uint16_t* lut, const uint16_t* sca
  *   y          out  bf16 [M][N], fully overwritten
  *   workspace  scratch of at least any4_gemm_workspace_bytes(M, N, K, bits) bytes,
  *              16-byte aligned; may be NULL when that size is 0.  Contents on entry
- *              are ignored, contents on exit are unspecified.
+ *              are ignored (no initialisation is needed), contents on exit are unspecified.
+ *              A workspace must not serve two calls that overlap in time, and after a
+ *              launch that did not run to its end (a device reset, an aborted process
+ *              sharing the memory) it should be cleared or replaced: a half-finished
+ *              call can leave arrival counters that look like its successor's own.
  */
 int any4_gemm(const uint16_t* x, const uint32_t* codes, const uint16_t* lut,
               const uint16_t* scale, const uint16_t* offset,
@@ -203,17 +214,6 @@ int any4_quantize(const float* w, const float* act, const float* u, int64_t N, i
 
 /* Largest K any4_quantize accepts. */
 int64_t any4_quantize_max_k(void);
-
-/*
- * any4_stream_read - measurement helper, not part of the method: reads the first
- * (bytes / 16) * 16 bytes at p once with 16-byte loads and does nothing else.  The benchmark
- * times it on the same buffers as the GEMM to report what a launch that only streams those
- * bytes costs on the device.  The xor of all words read is written to sink[0] only if it equals
- * `magic` (pass any value; the store exists so that the loads are kept).
- *   p      in   device buffer, 16-byte aligned, at least 16 bytes
- *   sink   out  uint32 [1], normally left untouched
- */
-int any4_stream_read(const void* p, size_t bytes, uint32_t magic, uint32_t* sink, void* stream);
 
 /* Static, human-readable text for a return code. */
 const char* any4_strerror(int code);

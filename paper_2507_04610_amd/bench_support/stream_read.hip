@@ -1,11 +1,11 @@
-// Measurement helper: a kernel that only reads a buffer, used by the benchmark to find what
-// a launch that streams the same bytes as a GEMM costs on this GPU when it does no arithmetic
-// (launch, first-byte latency and the streaming rate a simple kernel reaches).  Not part of the
-// any4 method.
-#include "any4_device.h"
-#include "any4_internal.h"
-
-namespace any4 {
+// Measurement helper of bench.py, built as its own small library (libany4_bench.so): a kernel that
+// only reads a buffer.  The benchmark times it on the same buffers as the GEMM to report what a
+// launch that streams those bytes costs on this GPU when it does no arithmetic (launch, first-byte
+// latency and the streaming rate a simple kernel reaches).  Not part of the any4 method and not
+// part of libany4's C ABI.
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
 
 // 1024 persistent blocks of 512 threads; every thread keeps four 16-byte loads in flight and walks
 // the buffer with a grid stride; the xor of everything read is stored only if it equals a value
@@ -26,13 +26,14 @@ __global__ __launch_bounds__(512) void stream_read_kernel(const uint4* __restric
     if (acc == magic) sink[0] = acc;
 }
 
-hipError_t launch_stream_read(const void* p, size_t bytes, uint32_t magic, uint32_t* sink, hipStream_t stream) {
+// Reads the first (bytes / 16) * 16 bytes at p (device memory, 16-byte aligned, at least 16 bytes) once
+// on `stream`; sink is a device uint32[1] that is normally left untouched.  0 = launched, -1 = refused.
+extern "C" int bench_stream_read(const void* p, size_t bytes, uint32_t magic, uint32_t* sink, void* stream) {
+    if (!p || !sink || bytes < 16 || (reinterpret_cast<uintptr_t>(p) & 15u)) return -1;
     const int64_t n16 = (int64_t)(bytes / 16);
     const int64_t want = (n16 + 511) / 512;
     const unsigned blocks = (unsigned)(want < 1 ? 1 : (want > 1024 ? 1024 : want));
-    hipLaunchKernelGGL(stream_read_kernel, dim3(blocks), dim3(512), 0, stream,
+    hipLaunchKernelGGL(stream_read_kernel, dim3(blocks), dim3(512), 0, static_cast<hipStream_t>(stream),
                        static_cast<const uint4*>(p), n16, magic, sink);
-    return hipGetLastError();
+    return hipGetLastError() == hipSuccess ? 0 : -1;
 }
-
-}  // namespace any4

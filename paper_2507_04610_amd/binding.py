@@ -1,7 +1,8 @@
 """Thin Python binding of libany4's C ABI (include/any4.h).
 
 Argument marshalling only: every function takes torch tensors that already live in device
-memory, checks dtype / shape / contiguity, and passes raw pointers plus the current HIP stream
+memory, checks dtype / shape / contiguity (every array the kernels index is compared with the
+shape (N, K, bits, group) implies), and passes raw pointers plus the current HIP stream
 to the library.  No arithmetic of the method happens here, and there is no fallback: if the
 shared library is missing or a call is made with host tensors, this module raises.
 """
@@ -17,7 +18,7 @@ LIB_PATH = os.path.join(_PKG, "libany4.so")
 GROUP = 128
 
 EXPORTS = ("any4_pack", "any4_dequant", "any4_gemm", "any4_gemm_workspace_bytes", "any4_repack", "any4_repack_bytes", "any4_gemm_repacked", "any4_dequant_grouped", "any4_gemm_grouped", "any4_dequant_f16", "any4_gemm_f16",
-           "any4_quantize", "any4_quantize_max_k", "any4_stream_read", "any4_strerror", "any4_version")
+           "any4_quantize", "any4_quantize_max_k", "any4_strerror", "any4_version")
 
 
 class Any4Error(RuntimeError):
@@ -63,8 +64,6 @@ def load_library() -> ctypes.CDLL:
     lib.any4_quantize.argtypes = [vp, vp, vp, i64, i64, ci, ci, ci, vp, vp, vp, vp, vp, vp]
     lib.any4_quantize_max_k.restype = i64
     lib.any4_quantize_max_k.argtypes = []
-    lib.any4_stream_read.restype = ci
-    lib.any4_stream_read.argtypes = [vp, ctypes.c_size_t, ctypes.c_uint32, vp, vp]
     lib.any4_strerror.restype = ctypes.c_char_p
     lib.any4_strerror.argtypes = [ci]
     lib.any4_version.restype = ci
@@ -86,6 +85,30 @@ def _dev(t: torch.Tensor, dtype, name: str) -> int:
     if not t.is_contiguous():
         raise Any4Error(f"{name} must be contiguous")
     return t.data_ptr()
+
+
+def _shape(t: torch.Tensor, want, name: str) -> None:
+    if tuple(t.shape) != tuple(want):
+        raise Any4Error(f"{name} must have shape {tuple(want)}, got {tuple(t.shape)}")
+
+
+def _check_quant_shapes(codes, lut, scale, offset, N, K, bits, group, repacked=False) -> None:
+    """the kernels index these arrays from (N, K, bits, group) alone: a wrong shape would make them read
+    out of bounds on the device, so it is refused here"""
+    if bits not in (4, 3, 2):
+        raise Any4Error(f"bits must be 4, 3 or 2, got {bits}")
+    if K < 1 or K % GROUP or group < 1 or K % group:
+        raise Any4Error(f"K = {K} must be a positive multiple of 128 and of the group size {group}")
+    if repacked:
+        need = (N + 15) // 16 * 16 * row_words(K, bits)
+        if codes.numel() != need:
+            raise Any4Error(f"rcodes must hold {need} words (any4_repack_bytes), got {codes.numel()}")
+    else:
+        _shape(codes, (N, row_words(K, bits)), "codes")
+    if lut is not None:
+        _shape(lut, (N, 1 << bits), "lut")
+    _shape(scale, (N, K // group), "scale")
+    _shape(offset, (N, K // group), "offset")
 
 
 def _stream() -> int:
@@ -116,6 +139,7 @@ def any4_pack(codes_u8: torch.Tensor, bits: int = 4, out: torch.Tensor | None = 
     src = _dev(codes_u8, torch.uint8, "codes_u8")
     if out is None:
         out = torch.empty((N, max(K * bits // 32, 0)), dtype=torch.int32, device=codes_u8.device)
+    _shape(out, (N, max(K * bits // 32, 0)), "out")
     dst = _dev(out, torch.int32, "out")
     _check(lib.any4_pack(src, N, K, bits, dst, _stream()), "any4_pack")
     return out
@@ -130,11 +154,13 @@ def any4_dequant(codes: torch.Tensor, lut: torch.Tensor | None, scale: torch.Ten
     N = codes.shape[0]
     pc = _dev(codes, torch.int32, "codes")
     dt = scale.dtype if isinstance(scale, torch.Tensor) and scale.dtype == torch.float16 else torch.bfloat16
+    _check_quant_shapes(codes, lut, scale, offset, N, K, bits, group)
     pl = _dev(lut, dt, "lut") if lut is not None else None
     ps = _dev(scale, dt, "scale")
     po = _dev(offset, dt, "offset")
     if out is None:
         out = torch.empty((N, K), dtype=torch.float32, device=codes.device)
+    _shape(out, (N, K), "out")
     pw = _dev(out, torch.float32, "out")
     if dt == torch.float16:
         if group != GROUP:
@@ -157,11 +183,14 @@ def _gemm(entry: str, x, codes, N, lut, scale, offset, bits, out, workspace, gro
         entry = "any4_gemm_f16"
     px = _dev(x, dt, "x")
     pc = _dev(codes, torch.int32, "codes")
+    _check_quant_shapes(codes, lut, scale, offset, N, K, bits, GROUP if group is None else group,
+                        repacked=entry == "any4_gemm_repacked")
     pl = _dev(lut, dt, "lut") if lut is not None else None
     ps = _dev(scale, dt, "scale")
     po = _dev(offset, dt, "offset")
     if out is None:
         out = torch.empty((M, N), dtype=dt, device=x.device)
+    _shape(out, (M, N), "out")
     py = _dev(out, dt, "out")
     need = int(lib.any4_gemm_workspace_bytes(M, N, K, bits))
     if workspace is None and need > 0:
@@ -239,13 +268,3 @@ def any4_quantize(w: torch.Tensor, act: torch.Tensor | None, u: torch.Tensor, bi
     _check(lib.any4_quantize(pw, pa, pu, N, K, bits, int(symmetric), iters, codes.data_ptr(), lut.data_ptr(),
                              scale.data_ptr(), offset.data_ptr(), msteps.data_ptr(), _stream()), "any4_quantize")
     return {"codes_u8": codes, "lut": lut, "scale": scale, "offset": offset, "msteps": msteps}
-
-
-def any4_stream_read(buf: torch.Tensor, sink: torch.Tensor, magic: int = 0x5EED1234) -> None:
-    """Measurement helper: read `buf` once on the current stream (see include/any4.h)."""
-    lib = load_library()
-    if not buf.is_cuda or not buf.is_contiguous():
-        raise Any4Error("buf must be a contiguous tensor in device memory")
-    ps = _dev(sink, torch.int32, "sink")
-    _check(lib.any4_stream_read(buf.data_ptr(), buf.numel() * buf.element_size(), magic, ps, _stream()),
-           "any4_stream_read")

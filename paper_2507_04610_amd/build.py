@@ -10,6 +10,8 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libany4.so")
+BENCH_SRC = os.path.join(PKG, "bench_support", "stream_read.hip")
+BENCH_LIB = os.path.join(PKG, "bench_support", "libany4_bench.so")
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -42,6 +44,11 @@ def build_library(verbose: bool = True) -> str:
         if p.wait() != 0:
             raise RuntimeError(f"hipcc failed on {src}")
     cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.check_call(cmd)
+    # bench.py's measurement helper (a read-only kernel): a library of its own, not part of libany4
+    cmd = [hipcc, *HIPCC_FLAGS, "-shared", BENCH_SRC, "-o", BENCH_LIB]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)

@@ -2,7 +2,6 @@
 #include "any4.h"
 #include "any4_internal.h"
 #include "any4_splitk.h"
-#include <stdlib.h>
 
 namespace any4 {
 
@@ -27,15 +26,13 @@ constexpr int kChunkedMaxM = 128;      // above this the matrix-core kernel is a
 constexpr int kFineRows = 8;           // groups of 64 weights: rows of x per launch of the streaming kernel
 
 // Compute units of the current device (256 on MI355X); only shapes the work split, never results.
+// Asked of the runtime on every call (the current device may differ from call to call).
 int device_compute_units() {
-    static const int cus = [] {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
-            n = 256;
-        return n;
-    }();
-    return cus;
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
+        n = 256;
+    return n;
 }
 
 GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int bits) {
@@ -145,14 +142,6 @@ int any4_dequant_f16(const uint32_t* codes, const uint16_t* lut, const uint16_t*
 int any4_dequant(const uint32_t* codes, const uint16_t* lut, const uint16_t* scale,
                  const uint16_t* offset, int64_t N, int64_t K, int bits, float* w, void* stream) {
     return any4_dequant_grouped(codes, lut, scale, offset, N, K, bits, ANY4_GROUP, w, stream);
-}
-
-int any4_stream_read(const void* p, size_t bytes, uint32_t magic, uint32_t* sink, void* stream) {
-    if (!p || !sink) return ANY4_ERR_NULL;
-    if (bytes < 16) return ANY4_ERR_SHAPE;
-    if (!aligned16(p)) return ANY4_ERR_ALIGN;
-    return launch_stream_read(p, bytes, magic, sink, static_cast<hipStream_t>(stream)) == hipSuccess
-               ? ANY4_OK : ANY4_ERR_HIP;
 }
 
 int64_t any4_quantize_max_k(void) { return (int64_t)quantize_max_k(); }

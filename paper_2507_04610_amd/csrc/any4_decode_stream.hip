@@ -62,7 +62,6 @@
 #include "any4_device.h"
 #include "any4_internal.h"
 #include "any4_splitk.h"
-#include <stdlib.h>
 #include <type_traits>
 
 namespace any4 {
@@ -100,16 +99,6 @@ constexpr int aux_base(int bits) { return table_bytes(bits) + kRedBytes; }
 constexpr int list_base(int bits, bool fine) { return aux_base(bits) + kAuxDist * aux_slot(fine); }
 constexpr int lds_bytes(int bits, bool fine = false) { return list_base(bits, fine) + (1 + kListTiles) * 4; }
 
-#ifdef ANY4_STAMPS
-// timing probes for tuning builds: time stamps at the natural LDS synchronisation points of a tile
-// step, collected in LDS and written out when the block ends
-__device__ long long* g_any4_dbg_stream = nullptr;
-constexpr int kStampSteps = 32;
-#define ST_STAMP(i) do { if (lane == 0 && (t - t0) < kStampSteps) stamps[((w * kStampSteps) + (t - t0)) * 4 + (i)] = wall_clock64(); } while (0)
-#else
-#define ST_STAMP(i) do {} while (0)
-#endif
-
 struct Params {
     const uint16_t* x;
     const uint32_t* codes;
@@ -125,15 +114,7 @@ struct Params {
                                      // of its row (rows of G >> lr entries)
     int slabs, slab_groups;          // groups per slab (the last slab may have fewer)
     int blocks_per_slab, tiles;
-#ifdef ANY4_TUNING
-    int stop;                        // tuning builds: leave the kernel early at a numbered point
-#endif
 };
-#ifdef ANY4_TUNING
-#define ANY4_STOP(i) do { if (p.stop == (i)) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); return; } } while (0)
-#else
-#define ANY4_STOP(i) do {} while (0)
-#endif
 
 // LDS barrier that does not wait for outstanding global loads (the prefetched codes stay in flight)
 __device__ __forceinline__ void lds_barrier() {
@@ -187,21 +168,11 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
     float* red = reinterpret_cast<float*>(smem + table_bytes(BITS));    // [2][WAVES][4][64]
     unsigned char* const aux = smem + aux_base(BITS);                   // [kAuxDist] slots
     int* lastlist = reinterpret_cast<int*>(smem + list_base(BITS, FINE && AUX));     // [0] = count
-#ifdef ANY4_STAMPS
-    const long long stamp_entry = wall_clock64();
-    long long* stamps = reinterpret_cast<long long*>(smem + lds_bytes(BITS, FINE && AUX));
-    for (int i = threadIdx.x; i < WAVES * kStampSteps * 4; i += WAVES * 64) stamps[i] = 0;
-    __syncthreads();
-#define ST_MARK(i) do { if ((threadIdx.x & 63) == 0) stamps[(((threadIdx.x >> 6) * kStampSteps) + kStampSteps - 1) * 4 + (i)] = wall_clock64(); } while (0)
-#else
-#define ST_MARK(i) do {} while (0)
-#endif
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 15, q = lane >> 4;
 
-    ANY4_STOP(1);
     const int slab = blockIdx.x / p.blocks_per_slab, bb = blockIdx.x - slab * p.blocks_per_slab;
     if (slab >= p.slabs) return;
     const int t0 = (int)((int64_t)bb * p.tiles / p.blocks_per_slab);
@@ -555,7 +526,6 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
             load_so(sraw[d], oraw[d], t);
         }
     }
-    ANY4_STOP(4);
 #pragma unroll
     for (int gi = 0; gi < GW; ++gi)
 #pragma unroll
@@ -630,7 +600,6 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
                                        __builtin_amdgcn_perm(v.w, v.y, 0x05040100u), __builtin_amdgcn_perm(v.w, v.y, 0x07060302u));
             }
     }
-    ANY4_STOP(5);
     if constexpr (AUX) {
         build_table(lut0, 0);
         if (w < kAuxDist && w < ntiles) aux_write(w);
@@ -638,14 +607,8 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
         build_table(lut_ring[0], 0);
         load_lut(lut_ring[0], min(t0 + kDepth, t1 - 1));
     }
-    ANY4_STOP(6);
     if (tid == 0) lastlist[0] = 0;
     lds_barrier();
-#ifdef ANY4_STAMPS
-    if (lane == 0) stamps[((w * kStampSteps) + kStampSteps - 1) * 4 + 0] = stamp_entry;
-#endif
-    ST_MARK(1);
-    ANY4_STOP(2);
 
     const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
     // the tables are the first thing in the block's LDS (the kernel has no static LDS), so a table
@@ -734,7 +697,6 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
         const int i = t - t0, par = i & 1;
         const int tn = min(t + kDepth, t1 - 1);
         const uint32_t low = low0 + par * kLowPar;
-        ST_STAMP(0);
         uint4 bq[2][4];
         auto lookups = [&](int gi, uint4 (&b)[4]) {
             const Quarter c = cw[B][gi];
@@ -792,12 +754,7 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
         float* rd = red + ((par * WAVES + w) * 4) * 64 + lane;
 #pragma unroll
         for (int v = 0; v < 4; ++v) rd[v * 64] = acc[v];
-#ifdef ANY4_STAMPS
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        ST_STAMP(1);
-#endif
         lds_barrier();
-        ST_STAMP(2);
     };
 
     // full rounds of the ring in a loop with a single back edge (so that the compiler's count of
@@ -823,24 +780,13 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
             }
         }
     }
-    ANY4_STOP(3);
     reduce_store(t1 - 1);
-    ST_MARK(2);
-#ifdef ANY4_STAMPS
-    lds_barrier();
-    if (g_any4_dbg_stream)
-        for (int i = threadIdx.x; i < WAVES * kStampSteps * 4; i += WAVES * 64) {
-            if ((i & 3) == 3 && ((i >> 2) % kStampSteps) == kStampSteps - 1) continue;     // written at the very end
-            g_any4_dbg_stream[(int64_t)blockIdx.x * (16 * kStampSteps * 4) + i] = stamps[i];
-        }
-#endif
 
     // ---- more than one slab: arrive at the counters of all tiles of this block, then finish the
     //      tiles for which this block was the last
     if (p.slabs > 1) {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's partial sums have been written
         lds_barrier();                                     // ... and so have the whole block's
-        ANY4_STOP(11);
         for (int tb0 = t0; tb0 < t1; tb0 += kListTiles) {      // in rounds of what the list holds
             const int tb1 = min(t1, tb0 + kListTiles);
             for (int i = tb0 + tid; i < tb1; i += kThreads) {
@@ -850,7 +796,6 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
                 }
             }
             lds_barrier();
-            ANY4_STOP(12);
             // All outputs of all listed tiles.  A thread takes UC outputs at a time and issues the
             // loads of KC slabs of all of them before it adds anything (one wait per KC * UC loads:
             // the partial sums come from other compute units, a load costs a trip to memory);
@@ -903,19 +848,7 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
             lds_barrier();
         }
     }
-#ifdef ANY4_STAMPS
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    if (lane == 0 && g_any4_dbg_stream)
-        g_any4_dbg_stream[(int64_t)blockIdx.x * (16 * kStampSteps * 4) + ((w * kStampSteps) + kStampSteps - 1) * 4 + 3] = wall_clock64();
-#endif
 }
-
-#ifdef ANY4_STAMPS
-extern "C" int any4_debug_set_buffer_stream(void* p) {
-    long long* q = static_cast<long long*>(p);
-    return (int)hipMemcpyToSymbol(HIP_SYMBOL(g_any4_dbg_stream), &q, sizeof(q));
-}
-#endif
 
 }  // namespace stream
 
@@ -928,14 +861,8 @@ StreamPlan plan_stream(int64_t M, int64_t N, int64_t K, int cus) {
     const int64_t tiles = (N + stream::kTile - 1) / stream::kTile;
     if (M > stream::kTile || tiles > 0x7FFFFFFF) return best;
     double best_cost = 1e300;
-    int only_gw = 0;
-#ifdef ANY4_TUNING
-    if (const char* e = getenv("ANY4_TUNE_GW")) only_gw = atoi(e);
-    if (only_gw < 0) return best;
-#endif
     const bool aux = G % 4 == 0;
     for (int gw : {4, 2, 1}) {
-        if (only_gw && gw != only_gw) continue;
         const int slab_max = stream::kWaves * gw;
         int slabs = (G + slab_max - 1) / slab_max;
         // equal slabs, each a multiple of gw groups (of 4 groups in AUX mode), except possibly the last
@@ -969,15 +896,9 @@ StreamPlan plan_stream(int64_t M, int64_t N, int64_t K, int cus) {
 template <int BITS, int GW, bool AUX, bool NOLUT = false, bool REPACK = false, bool COARSE = false, bool FINE = false,
           bool F16 = false>
 static hipError_t launch_stream_t(const Params& p, int grid, hipStream_t stream) {
-    auto kern = stream::decode_stream_kernel<BITS, GW, AUX, NOLUT, REPACK, COARSE, FINE, F16>;
-#ifdef ANY4_STAMPS
-    constexpr int lds = stream::lds_bytes(BITS, FINE && AUX) + stream::kWaves * stream::kStampSteps * 4 * 8;
-#else
+    constexpr auto kern = stream::decode_stream_kernel<BITS, GW, AUX, NOLUT, REPACK, COARSE, FINE, F16>;
     constexpr int lds = stream::lds_bytes(BITS, FINE && AUX);
-#endif
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    if (e != hipSuccess) return e;
+    if (hipError_t e = ensure_lds<kern>(lds); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(stream::kWaves * 64), lds, stream, p);
     return hipGetLastError();
 }
@@ -1008,9 +929,6 @@ hipError_t launch_decode_stream(const uint16_t* x, const uint32_t* codes, const 
     p.N = N; p.K = K; p.M = (int)M; p.G = (int)(K / kGroup); p.lr = lr;
     p.slabs = sp.slabs; p.slab_groups = sp.slab_groups; p.blocks_per_slab = sp.blocks_per_slab;
     p.tiles = (int)sp.tiles;
-#ifdef ANY4_TUNING
-    if (const char* e = getenv("ANY4_TUNE_STOP")) p.stop = atoi(e);
-#endif
     const int grid = sp.slabs * sp.blocks_per_slab;
     if (f16) {
         // fp16: the table-based kernels on the plain layout with groups of 128

@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <stddef.h>
 #include <stdint.h>
+#include <atomic>
 
 namespace any4 {
 
@@ -18,6 +19,20 @@ struct StreamPlan {
 };
 StreamPlan plan_stream(int64_t M, int64_t N, int64_t K, int cus);
 int device_compute_units();
+
+// Raises the dynamic-LDS limit of kernel `Kern` to `bytes` the first time it is asked for on a device
+// (one bit per device ordinal; devices past 63 ask the runtime every time).  Launch functions call
+// it before their first launch, so that a refusal leaves nothing enqueued.
+template <auto Kern> hipError_t ensure_lds(int bytes) {
+    static std::atomic<unsigned long long> done{0};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev >= 0 && dev < 64 && ((done.load(std::memory_order_acquire) >> dev) & 1ull)) return hipSuccess;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(Kern), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess && dev >= 0 && dev < 64) done.fetch_or(1ull << dev, std::memory_order_release);
+    return e;
+}
 
 // How any4_gemm runs a given problem; a pure function of (M, N, K, bits) so that
 // any4_gemm_workspace_bytes() and any4_gemm() always agree.
@@ -64,9 +79,6 @@ struct PrefillPlan {
 };
 PrefillPlan plan_prefill(int64_t M, int64_t N, int64_t K, int cus);
 size_t prefill_workspace_bytes(int64_t M, int64_t N, int64_t K, int cus);
-
-// Read-only streaming kernel for the benchmark's "what does a launch that reads these bytes cost" figure.
-hipError_t launch_stream_read(const void* p, size_t bytes, uint32_t magic, uint32_t* sink, hipStream_t stream);
 
 // Quantiser: one block per row, the row lives in LDS, which bounds K.
 size_t quantize_max_k();

@@ -503,16 +503,17 @@ hipError_t launch_prefill(const uint16_t* x, const uint32_t* codes, const uint16
     uint16_t* xsums = static_cast<uint16_t*>(workspace);
     unsigned long long* counters = reinterpret_cast<unsigned long long*>(static_cast<char*>(workspace) + pp.xsums_bytes);
     float* partial = reinterpret_cast<float*>(static_cast<char*>(workspace) + pp.xsums_bytes + pp.counter_bytes);
-    if (f16) hipLaunchKernelGGL(group_sums_kernel<true>, dim3((unsigned)sblocks), dim3(256), 0, stream, x, M, K, KP, 0, xsums);
-    else hipLaunchKernelGGL(group_sums_kernel<false>, dim3((unsigned)sblocks), dim3(256), 0, stream, x, M, K, KP, fine ? 1 : 0, xsums);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
     const dim3 grid((unsigned)nblocks), block(PTHREADS);
     const int gm = (int)pp.gm, tail_first = (int)(pp.tiles - pp.tail_tiles), tail_s = pp.tail_s;
+    // the LDS limit first: whatever can be refused is refused before anything is enqueued
+    hipError_t e = hipSuccess;
 #define ANY4_PREFILL_F(B, F, H)                                                                                   \
     do {                                                                                                          \
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(prefill_kernel<B, F, H>),                           \
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)prefill_lds_bytes(B));           \
+        e = ensure_lds<prefill_kernel<B, F, H>>((int)prefill_lds_bytes(B));                                       \
+        if (e != hipSuccess) return e;                                                                            \
+        if (f16) hipLaunchKernelGGL(group_sums_kernel<true>, dim3((unsigned)sblocks), dim3(256), 0, stream, x, M, K, KP, 0, xsums); \
+        else hipLaunchKernelGGL(group_sums_kernel<false>, dim3((unsigned)sblocks), dim3(256), 0, stream, x, M, K, KP, fine ? 1 : 0, xsums); \
+        e = hipGetLastError();                                                                                    \
         if (e != hipSuccess) return e;                                                                            \
         hipLaunchKernelGGL((prefill_kernel<B, F, H>), grid, block, prefill_lds_bytes(B), stream, x, codes, lut, scale, \
                            offset, xsums, KP, M, N, K, F ? 0 : lr, repacked ? 1 : 0, gm, tail_first, tail_s, counters, partial, y); \

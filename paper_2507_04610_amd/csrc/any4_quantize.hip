@@ -272,8 +272,7 @@ hipError_t launch_quantize(const float* w, const float* act, const float* u, int
     hipError_t e = hipSuccess;
 #define ANY4_QUANT(B)                                                                                             \
     do {                                                                                                          \
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(quantize_kernel<B>),                                \
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);                            \
+        e = ensure_lds<quantize_kernel<B>>((int)quantize_lds_bytes((int64_t)quantize_max_k(), B));                \
         if (e != hipSuccess) return e;                                                                            \
         hipLaunchKernelGGL(quantize_kernel<B>, dim3((unsigned)N), dim3(QT), lds, stream, w, act, u, K, symmetric, \
                            iters, codes, lut, scale, offset, msteps);                                             \

@@ -21,8 +21,11 @@ __host__ __device__ inline size_t splitk_counter_bytes(int64_t tiles) { return (
 // Partial sums and counters are exchanged between blocks that may run on different XCDs (each
 // with its own L2).  Instead of device-wide fences - which write back and invalidate whole caches
 // and were measured to cost tens of microseconds per launch here - every access to them is a
-// relaxed agent-scope atomic (coherent by itself), and ordering comes from waiting for the
-// stores' completion before the counter is bumped.
+// relaxed agent-scope atomic (coherent by itself: such accesses are served by the memory side of
+// the cache hierarchy, never by a cache private to a compute unit or XCD), and ordering comes from
+// waiting for the stores' completion (s_waitcnt vmcnt(0) plus a block barrier) before the counter
+// is bumped: a store that has completed at that level is visible to every later agent-scope load,
+// and the reader's loads are issued only after its own atomic on the counter has returned.
 __device__ __forceinline__ void splitk_store(float* p, float v) {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
@@ -38,15 +41,19 @@ __device__ __forceinline__ float splitk_load(const float* p) {
 // something else) is claimed with a compare-and-swap instead.
 constexpr unsigned long long kArriveTag = 0x00A4C0DE5EED17ull;          // 56 bits
 __device__ __forceinline__ bool arrive_one(unsigned long long* c, int ksplit) {
+    // a word is this call's own only if it carries the tag AND fewer than ksplit arrivals: a tagged word
+    // with more (left by a launch that never finished, or by a call with another slab count that
+    // shared the memory) is treated like memory that held something else
+    auto own = [&](unsigned long long v) -> bool { return (v >> 8) == kArriveTag && (v & 0xFFull) < (unsigned long long)ksplit; };
     unsigned long long old = __hip_atomic_fetch_add(c, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     unsigned long long cnt;
-    if ((old >> 8) == kArriveTag) {
+    if (own(old)) {
         cnt = (old & 0xFFull) + 1ull;
     } else {
         // the add above went into a foreign word and is dropped with it
         old += 1ull;
         for (;;) {
-            cnt = ((old >> 8) == kArriveTag) ? (old & 0xFFull) + 1ull : 1ull;
+            cnt = own(old) ? (old & 0xFFull) + 1ull : 1ull;
             const unsigned long long nv = (kArriveTag << 8) | cnt;
             if (__hip_atomic_compare_exchange_strong(c, &old, nv, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
                                                      __HIP_MEMORY_SCOPE_AGENT))

@@ -41,7 +41,7 @@ def test_no_kernel_uses_scratch_memory_or_spills():
     if not os.path.exists(binding.LIB_PATH):
         pytest.skip("libany4.so has not been built")
     images = device_code_objects(binding.LIB_PATH)
-    assert len(images) >= 8, "one code object per kernel source file"
+    assert len(images) >= 7, "one code object per kernel source file"
     kernels = {}
     tmp = tempfile.mkdtemp()
     try:
