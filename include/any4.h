@@ -215,6 +215,26 @@ int any4_quantize(const float* w, const float* act, const float* u, int64_t N, i
 /* Largest K any4_quantize accepts. */
 int64_t any4_quantize_max_k(void);
 
+/*
+ * any4_gemm_noalloc - any4_gemm for callers that cannot allocate device memory or have no
+ * workspace to hand over: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same operation, arguments, result (bit for bit) and error codes as any4_gemm,
+ * without the workspace arguments: the scratch lives in a device array inside the library,
+ * ANY4_NOALLOC_SCRATCH_BYTES per GPU, held from the library's load until the process ends.  The
+ * call allocates and frees nothing.
+ *   - A problem whose any4_gemm_workspace_bytes() exceeds ANY4_NOALLOC_SCRATCH_BYTES returns
+ *     ANY4_ERR_WORKSPACE (nothing launched): use any4_gemm with a workspace of your own.
+ *   - All calls on one GPU share that GPU's array: two any4_gemm_noalloc calls that overlap in
+ *     time on the same GPU (different streams, or graphs replayed concurrently) race on it and
+ *     give undefined results.  Calls that follow each other on one stream are fine.
+ *   - The first call on a GPU looks the array's address up (a host-side call into the HIP
+ *     runtime); make one call outside any graph capture before capturing.
+ */
+#define ANY4_NOALLOC_SCRATCH_BYTES (48u << 20)
+int any4_gemm_noalloc(const uint16_t* x, const uint32_t* codes, const uint16_t* lut,
+                      const uint16_t* scale, const uint16_t* offset,
+                      int64_t M, int64_t N, int64_t K, int bits, uint16_t* y, void* stream);
+
 /* Static, human-readable text for a return code. */
 const char* any4_strerror(int code);
 

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_PKG, "libany4.so")
 GROUP = 128
 
 EXPORTS = ("any4_pack", "any4_dequant", "any4_gemm", "any4_gemm_workspace_bytes", "any4_repack", "any4_repack_bytes", "any4_gemm_repacked", "any4_dequant_grouped", "any4_gemm_grouped", "any4_dequant_f16", "any4_gemm_f16",
-           "any4_quantize", "any4_quantize_max_k", "any4_strerror", "any4_version")
+           "any4_quantize", "any4_quantize_max_k", "any4_gemm_noalloc", "any4_strerror", "any4_version")
 
 
 class Any4Error(RuntimeError):
@@ -56,6 +56,8 @@ def load_library() -> ctypes.CDLL:
     lib.any4_gemm_grouped.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, ci, ci, vp, vp, ctypes.c_size_t, vp]
     lib.any4_gemm_repacked.restype = ci
     lib.any4_gemm_repacked.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, ci, vp, vp, ctypes.c_size_t, vp]
+    lib.any4_gemm_noalloc.restype = ci
+    lib.any4_gemm_noalloc.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, ci, vp, vp]
     lib.any4_repack.restype = ci
     lib.any4_repack.argtypes = [vp, i64, i64, ci, vp, vp]
     lib.any4_repack_bytes.restype = ctypes.c_size_t
@@ -214,6 +216,30 @@ def any4_gemm(x: torch.Tensor, codes: torch.Tensor, lut: torch.Tensor | None, sc
     if group == GROUP:
         return _gemm("any4_gemm", x, codes, codes.shape[0], lut, scale, offset, bits, out, workspace)
     return _gemm("any4_gemm_grouped", x, codes, codes.shape[0], lut, scale, offset, bits, out, workspace, group)
+
+
+NOALLOC_SCRATCH_BYTES = 48 << 20
+
+
+def any4_gemm_noalloc(x: torch.Tensor, codes: torch.Tensor, lut: torch.Tensor | None, scale: torch.Tensor,
+                      offset: torch.Tensor, bits: int = 4, out: torch.Tensor | None = None) -> torch.Tensor:
+    """any4_gemm without a workspace: the library's own fixed scratch array serves (see include/any4.h;
+    calls on one GPU must not overlap in time).  `out` should be passed by callers that must not allocate."""
+    lib = load_library()
+    M, K = x.shape
+    N = codes.shape[0]
+    px = _dev(x, torch.bfloat16, "x")
+    pc = _dev(codes, torch.int32, "codes")
+    _check_quant_shapes(codes, lut, scale, offset, N, K, bits, GROUP)
+    pl = _dev(lut, torch.bfloat16, "lut") if lut is not None else None
+    ps = _dev(scale, torch.bfloat16, "scale")
+    po = _dev(offset, torch.bfloat16, "offset")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.bfloat16, device=x.device)
+    _shape(out, (M, N), "out")
+    py = _dev(out, torch.bfloat16, "out")
+    _check(lib.any4_gemm_noalloc(px, pc, pl, ps, po, M, N, K, bits, py, _stream()), "any4_gemm_noalloc")
+    return out
 
 
 def any4_repack_bytes(N: int, K: int, bits: int = 4) -> int:

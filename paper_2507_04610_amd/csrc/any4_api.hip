@@ -43,6 +43,7 @@ GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int bits) {
             p.decode = p.stream = true;
             p.ksplit = p.sp.slabs;
             p.workspace = p.sp.workspace;
+            p.counter_bytes = p.sp.slabs > 1 ? splitk_counter_bytes(p.sp.tiles) : 0;
             return p;
         }
     }
@@ -76,6 +77,7 @@ GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int bits) {
                 p.sp_tail = tail;
                 p.ksplit = full.slabs;
                 p.workspace = full.workspace > tail.workspace ? full.workspace : tail.workspace;
+                p.counter_bytes = full.slabs > 1 || tail.slabs > 1 ? splitk_counter_bytes(full.tiles) : 0;
                 // (groups of 64 weights go to the matrix-core kernel for these M: room for either)
                 const size_t wm = prefill_workspace_bytes(M, N, K, cus);
                 if (wm > p.workspace) p.workspace = wm;
@@ -97,13 +99,71 @@ GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int bits) {
         p.ksplit = (int)want;
     }
     if (p.decode) p.workspace = p.ksplit > 1 ? (size_t)p.ksplit * (size_t)M * (size_t)N * sizeof(float) : 0;
-    else p.workspace = prefill_workspace_bytes(M, N, K, device_compute_units());
+    else {
+        const PrefillPlan pp = plan_prefill(M, N, K, device_compute_units());
+        p.workspace = pp.xsums_bytes + pp.counter_bytes + pp.partial_bytes;
+        p.counter_offset = pp.xsums_bytes;
+        p.counter_bytes = pp.counter_bytes;
+    }
     return p;
 }
 
 }  // namespace any4
 
 using namespace any4;
+
+namespace any4 {
+
+int gemm_dispatch(const uint16_t* x, const uint32_t* codes, bool repacked, const uint16_t* lut,
+                           const uint16_t* scale, const uint16_t* offset, int64_t M, int64_t N, int64_t K,
+                           int bits, int group, uint16_t* y, void* workspace, size_t workspace_bytes, void* stream,
+                           bool f16) {
+    if (!x || !codes || !scale || !offset || !y) return ANY4_ERR_NULL;
+    if (f16 && !lut) return ANY4_ERR_NULL;                           // fp16: table-based only
+    if (!lut && (bits != 4 || repacked)) return ANY4_ERR_NULL;       // no table = the 4-bit integer grid, plain layout only
+    if (int rc = shape_check(N, K, bits)) return rc;
+    if (M < 1) return ANY4_ERR_SHAPE;
+    int lr;
+    if (!group_shift(K, group, &lr)) return ANY4_ERR_SHAPE;
+    if (!lut && lr != 0) return ANY4_ERR_NULL;                           // the table-free path has groups of 128
+    if (!aligned16(x) || !aligned16(codes) || !aligned16(lut) || !aligned16(scale) ||
+        !aligned16(offset) || !aligned16(y) || !aligned16(workspace))
+        return ANY4_ERR_ALIGN;
+    const GemmPlan plan = plan_gemm(M, N, K, bits);
+    // K beyond the streaming kernel's range: only the plain layout with groups of 128
+    if ((repacked || lr != 0 || f16) && plan.decode && !plan.stream) return ANY4_ERR_SHAPE;
+    if (plan.workspace > 0 && (!workspace || workspace_bytes < plan.workspace)) return ANY4_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e;
+    if (lr < 0 && plan.stream && !plan.chunked) {
+        // groups of 64 weights, M <= 16: the streaming kernel takes 8 rows of x a launch
+        e = hipSuccess;
+        for (int64_t m0 = 0; m0 < M && e == hipSuccess; m0 += kFineRows) {
+            const int64_t rows = M - m0 < kFineRows ? M - m0 : kFineRows;
+            e = launch_decode_stream(x + m0 * K, codes, lut, scale, offset, rows, N, K, bits, lr, false, false, plan.sp,
+                                     y + m0 * N, workspace, s);
+        }
+    } else if (lr < 0) {
+        e = launch_prefill(x, codes, lut, scale, offset, M, N, K, bits, lr, false, false, device_compute_units(), y, workspace, s);
+    } else if (plan.chunked) {
+        // launches run one after the other on the stream and leave the workspace's counters clean
+        e = hipSuccess;
+        for (int64_t m0 = 0; m0 < M && e == hipSuccess; m0 += kStreamMaxM) {
+            const int64_t rows = M - m0 < kStreamMaxM ? M - m0 : kStreamMaxM;
+            e = launch_decode_stream(x + m0 * K, codes, lut, scale, offset, rows, N, K, bits, lr, repacked, f16,
+                                     rows == kStreamMaxM ? plan.sp : plan.sp_tail, y + m0 * N, workspace, s);
+        }
+    } else if (plan.stream) {
+        e = launch_decode_stream(x, codes, lut, scale, offset, M, N, K, bits, lr, repacked, f16, plan.sp, y, workspace, s);
+    } else if (plan.decode) {
+        e = launch_decode(x, codes, lut, scale, offset, M, N, K, bits, plan, y, static_cast<float*>(workspace), s);
+    } else {
+        e = launch_prefill(x, codes, lut, scale, offset, M, N, K, bits, lr, repacked, f16, device_compute_units(), y, workspace, s);
+    }
+    return e == hipSuccess ? ANY4_OK : ANY4_ERR_HIP;
+}
+
+}  // namespace any4
 
 extern "C" {
 
@@ -165,77 +225,28 @@ size_t any4_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int bits) {
     return plan_gemm(M, N, K, bits).workspace;
 }
 
-static int gemm_any_layout(const uint16_t* x, const uint32_t* codes, bool repacked, const uint16_t* lut,
-                           const uint16_t* scale, const uint16_t* offset, int64_t M, int64_t N, int64_t K,
-                           int bits, int group, uint16_t* y, void* workspace, size_t workspace_bytes, void* stream,
-                           bool f16 = false) {
-    if (!x || !codes || !scale || !offset || !y) return ANY4_ERR_NULL;
-    if (f16 && !lut) return ANY4_ERR_NULL;                           // fp16: table-based only
-    if (!lut && (bits != 4 || repacked)) return ANY4_ERR_NULL;       // no table = the 4-bit integer grid, plain layout only
-    if (int rc = shape_check(N, K, bits)) return rc;
-    if (M < 1) return ANY4_ERR_SHAPE;
-    int lr;
-    if (!group_shift(K, group, &lr)) return ANY4_ERR_SHAPE;
-    if (!lut && lr != 0) return ANY4_ERR_NULL;                           // the table-free path has groups of 128
-    if (!aligned16(x) || !aligned16(codes) || !aligned16(lut) || !aligned16(scale) ||
-        !aligned16(offset) || !aligned16(y) || !aligned16(workspace))
-        return ANY4_ERR_ALIGN;
-    const GemmPlan plan = plan_gemm(M, N, K, bits);
-    // K beyond the streaming kernel's range: only the plain layout with groups of 128
-    if ((repacked || lr != 0 || f16) && plan.decode && !plan.stream) return ANY4_ERR_SHAPE;
-    if (plan.workspace > 0 && (!workspace || workspace_bytes < plan.workspace)) return ANY4_ERR_WORKSPACE;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    hipError_t e;
-    if (lr < 0 && plan.stream && !plan.chunked) {
-        // groups of 64 weights, M <= 16: the streaming kernel takes 8 rows of x a launch
-        e = hipSuccess;
-        for (int64_t m0 = 0; m0 < M && e == hipSuccess; m0 += kFineRows) {
-            const int64_t rows = M - m0 < kFineRows ? M - m0 : kFineRows;
-            e = launch_decode_stream(x + m0 * K, codes, lut, scale, offset, rows, N, K, bits, lr, false, false, plan.sp,
-                                     y + m0 * N, workspace, s);
-        }
-    } else if (lr < 0) {
-        e = launch_prefill(x, codes, lut, scale, offset, M, N, K, bits, lr, false, false, device_compute_units(), y, workspace, s);
-    } else if (plan.chunked) {
-        // launches run one after the other on the stream and leave the workspace's counters clean
-        e = hipSuccess;
-        for (int64_t m0 = 0; m0 < M && e == hipSuccess; m0 += kStreamMaxM) {
-            const int64_t rows = M - m0 < kStreamMaxM ? M - m0 : kStreamMaxM;
-            e = launch_decode_stream(x + m0 * K, codes, lut, scale, offset, rows, N, K, bits, lr, repacked, f16,
-                                     rows == kStreamMaxM ? plan.sp : plan.sp_tail, y + m0 * N, workspace, s);
-        }
-    } else if (plan.stream) {
-        e = launch_decode_stream(x, codes, lut, scale, offset, M, N, K, bits, lr, repacked, f16, plan.sp, y, workspace, s);
-    } else if (plan.decode) {
-        e = launch_decode(x, codes, lut, scale, offset, M, N, K, bits, plan, y, static_cast<float*>(workspace), s);
-    } else {
-        e = launch_prefill(x, codes, lut, scale, offset, M, N, K, bits, lr, repacked, f16, device_compute_units(), y, workspace, s);
-    }
-    return e == hipSuccess ? ANY4_OK : ANY4_ERR_HIP;
-}
-
 int any4_gemm(const uint16_t* x, const uint32_t* codes, const uint16_t* lut, const uint16_t* scale,
               const uint16_t* offset, int64_t M, int64_t N, int64_t K, int bits, uint16_t* y,
               void* workspace, size_t workspace_bytes, void* stream) {
-    return gemm_any_layout(x, codes, false, lut, scale, offset, M, N, K, bits, ANY4_GROUP, y, workspace, workspace_bytes, stream);
+    return gemm_dispatch(x, codes, false, lut, scale, offset, M, N, K, bits, ANY4_GROUP, y, workspace, workspace_bytes, stream, false);
 }
 
 int any4_gemm_f16(const uint16_t* x, const uint32_t* codes, const uint16_t* lut, const uint16_t* scale,
                   const uint16_t* offset, int64_t M, int64_t N, int64_t K, int bits, uint16_t* y,
                   void* workspace, size_t workspace_bytes, void* stream) {
-    return gemm_any_layout(x, codes, false, lut, scale, offset, M, N, K, bits, ANY4_GROUP, y, workspace, workspace_bytes, stream, true);
+    return gemm_dispatch(x, codes, false, lut, scale, offset, M, N, K, bits, ANY4_GROUP, y, workspace, workspace_bytes, stream, true);
 }
 
 int any4_gemm_grouped(const uint16_t* x, const uint32_t* codes, const uint16_t* lut, const uint16_t* scale,
                       const uint16_t* offset, int64_t M, int64_t N, int64_t K, int bits, int group, uint16_t* y,
                       void* workspace, size_t workspace_bytes, void* stream) {
-    return gemm_any_layout(x, codes, false, lut, scale, offset, M, N, K, bits, group, y, workspace, workspace_bytes, stream);
+    return gemm_dispatch(x, codes, false, lut, scale, offset, M, N, K, bits, group, y, workspace, workspace_bytes, stream, false);
 }
 
 int any4_gemm_repacked(const uint16_t* x, const uint32_t* rcodes, const uint16_t* lut, const uint16_t* scale,
                        const uint16_t* offset, int64_t M, int64_t N, int64_t K, int bits, uint16_t* y,
                        void* workspace, size_t workspace_bytes, void* stream) {
-    return gemm_any_layout(x, rcodes, true, lut, scale, offset, M, N, K, bits, ANY4_GROUP, y, workspace, workspace_bytes, stream);
+    return gemm_dispatch(x, rcodes, true, lut, scale, offset, M, N, K, bits, ANY4_GROUP, y, workspace, workspace_bytes, stream, false);
 }
 
 size_t any4_repack_bytes(int64_t N, int64_t K, int bits) {

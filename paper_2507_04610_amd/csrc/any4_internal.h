@@ -44,8 +44,14 @@ struct GemmPlan {
     StreamPlan sp_tail;   // chunked only: the plan of the last launch when M is not a multiple of 16
     int ksplit;           // number of K slices whose fp32 partials are reduced in a 2nd pass
     size_t workspace;     // bytes of scratch: K-slice partials (decode) or group sums of x (matrix-core path)
+    size_t counter_offset, counter_bytes;   // where in the workspace the arrival counters sit (groups of 128)
 };
 GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int bits);
+// Validation, kernel choice and launches behind every any4_gemm* entry point; returns an ANY4_* code.
+int gemm_dispatch(const uint16_t* x, const uint32_t* codes, bool repacked, const uint16_t* lut,
+                  const uint16_t* scale, const uint16_t* offset, int64_t M, int64_t N, int64_t K,
+                  int bits, int group, uint16_t* y, void* workspace, size_t workspace_bytes, void* stream,
+                  bool f16);
 
 hipError_t launch_pack(const uint8_t* codes_u8, int64_t N, int64_t K, int bits,
                        uint32_t* codes, hipStream_t stream);

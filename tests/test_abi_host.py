@@ -83,6 +83,25 @@ def test_bad_arguments_are_rejected_before_any_launch(lib):
     assert lib.any4_gemm(A, A, A, A, A, 1, 4, 128, 4, A + 8, None, 0, None) == -4
 
 
+def test_noalloc_entry_point_checks_arguments_and_its_limit(lib):
+    """any4_gemm_noalloc: the same refusals as any4_gemm, plus ANY4_ERR_WORKSPACE for a problem whose
+    scratch exceeds the library's fixed array - all before anything touches the device"""
+    from paper_2507_04610_amd import binding
+    A = 0x1000
+    assert lib.any4_gemm_noalloc(A, A, A, A, A, 0, 4, 128, 4, A, None) == -2
+    assert lib.any4_gemm_noalloc(A, A, A, A, A, 1, 4, 192, 4, A, None) == -2
+    assert lib.any4_gemm_noalloc(A, A, A, A, A, 1, 4, 128, 5, A, None) == -3
+    assert lib.any4_gemm_noalloc(None, A, A, A, A, 1, 4, 128, 4, A, None) == -1
+    assert lib.any4_gemm_noalloc(A, A, None, A, A, 1, 4, 128, 3, A, None) == -1
+    assert lib.any4_gemm_noalloc(A, A, A, A, A + 2, 1, 4, 128, 4, A, None) == -4
+    M, N, K = 16, 500000, 8192
+    assert lib.any4_gemm_workspace_bytes(M, N, K, 4) > binding.NOALLOC_SCRATCH_BYTES
+    assert lib.any4_gemm_noalloc(A, A, A, A, A, M, N, K, 4, A, None) == -5
+    header = open(HEADER).read()
+    assert re.search(r"#define ANY4_NOALLOC_SCRATCH_BYTES \((\d+)u << 20\)", header)
+    assert int(re.search(r"#define ANY4_NOALLOC_SCRATCH_BYTES \((\d+)u << 20\)", header).group(1)) << 20 == binding.NOALLOC_SCRATCH_BYTES
+
+
 def test_repack_size(lib):
     # whole tiles of 16 rows; invalid arguments need nothing
     assert lib.any4_repack_bytes(16, 128, 4) == 16 * 64
