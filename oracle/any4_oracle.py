@@ -11,7 +11,10 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "any4_oracle.c")
-_LIB = os.path.join(_HERE, "libany4_oracle.so")
+# ANY4_ORACLE_SANITIZE=1 selects a second build of the same source with AddressSanitizer and
+# UndefinedBehaviorSanitizer (tests/test_oracle_sanitized.py runs the pins against it)
+_SANITIZE = os.environ.get("ANY4_ORACLE_SANITIZE", "") == "1"
+_LIB = os.path.join(_HERE, "libany4_oracle_san.so" if _SANITIZE else "libany4_oracle.so")
 GROUP = 128
 
 
@@ -19,7 +22,9 @@ def build(force: bool = False) -> str:
     """Compile the oracle with gcc (no fused contraction of a*b+c expressions, so the
     two-step check inside the dequantiser really rounds twice)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp",
+        opt = ["-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+               "-fno-omit-frame-pointer"] if _SANITIZE else ["-O2"]
+        subprocess.check_call(["gcc", *opt, "-std=c11", "-fPIC", "-shared", "-fopenmp",
                                "-ffp-contract=off", "-o", _LIB, _SRC, "-lm"])
     return _LIB
 

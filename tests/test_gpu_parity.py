@@ -2,8 +2,9 @@
 
 Bars: packed words and dequantised fp32 weights bit-exact; GEMM outputs within
 1e-2 * rms(y_fp64) + 2^-8 * |y_fp64| (half a bf16 ulp of output rounding) elementwise.
-Small shapes are compared element by element; the full benchmark shapes on sampled output
-rows (all M columns of each sampled row), with rms taken over the sampled block.
+Small shapes are compared element by element, and so are the full benchmark shapes for M <= 16
+(all M x N outputs); at M = 2048 one output column of every 128-wide block plus the first and last
+block are compared over all rows of x, with rms taken over the compared block.
 """
 import numpy as np
 import pytest
@@ -476,96 +477,114 @@ def test_gemm_repacked_needs_a_table(any4):
         any4.any4_gemm_repacked(dev_bf16(cs.x), rcodes, None, dev_bf16(cs.scale), dev_bf16(cs.offset), 4)
 
 
-# ------------------------------------------------------------------------------ full benchmark shapes, sampled rows
-SAMPLE_ROWS = 48
+# ------------------------------------------------------------------------------ full benchmark shapes
+# Every output is compared with the oracle where the oracle can compute it in seconds (M <= 16: all
+# M x N elements); at M = 2048 all rows of one column in every 128-wide block of output columns
+# (one per n-block of the matrix-core kernel) plus the whole first and last block of 128 columns.
+# Packed words and re-laid-out words are compared over the whole matrix; dequantised weights over
+# the whole matrix for the 8B linears and over the first 16 and last 4096 rows (the last tile
+# included) of a full-size launch for the 70B ones.
+ORACLE_THREADS = 16
+DEQUANT_WHOLE_LIMIT = 28672 * 4096
 
 
-def sampled_rows_check(any4, oracle, shape_name, N, K, bits, Ms, seed):
+def prefill_columns(N, rng):
+    blocks = (N + 127) // 128
+    one_per_block = [min(N - 1, b * 128 + int(rng.integers(0, 128))) for b in range(blocks)]
+    return np.unique(np.concatenate([np.arange(0, min(128, N)), np.arange(max(0, N - 128), N), one_per_block]))
+
+
+def gemm_tolerance_check(got, y64, rms, half_ulp, what):
+    tol = 1e-2 * rms + np.abs(y64) * half_ulp
+    err = np.abs(got - y64)
+    worst = np.unravel_index(np.argmax(err - tol), err.shape)
+    assert np.all(err <= tol), (what, "worst", worst, float(err[worst]), float(tol[worst]), "rms", rms)
+
+
+def full_shape_check(any4, oracle, shape_name, N, K, bits, Ms, seed, group=128, f16=False, relayout=True):
     Mmax = max(Ms)
-    cs = inputs.make_case(Mmax, N, K, bits, seed)
+    cs = inputs.make_case(Mmax, N, K, bits, seed, f16=f16)
+    if group == 64:
+        other = inputs.make_case(1, N, K, bits, seed + 1000)
+        sc = np.ascontiguousarray(np.stack([cs.scale, other.scale], axis=2).reshape(N, -1))
+        of = np.ascontiguousarray(np.stack([cs.offset, other.offset], axis=2).reshape(N, -1))
+    else:
+        sc, of = np.ascontiguousarray(cs.scale[:, ::group // 128]), np.ascontiguousarray(cs.offset[:, ::group // 128])
+    dev16 = dev_f16 if f16 else dev_bf16
+    half_ulp = 2.0 ** -11 if f16 else 2.0 ** -8
+    packed = oracle.pack(cs.codes_u8, bits)
     codes_dev = any4.any4_pack(torch.from_numpy(cs.codes_u8).cuda(), bits)
-    rcodes = any4.any4_repack(codes_dev, bits)
-    lut, scale, offset = dev_bf16(cs.lut), dev_bf16(cs.scale), dev_bf16(cs.offset)
+    assert np.array_equal(host_u32(codes_dev), packed), (shape_name, "packed words")
+    lut, scale, offset = dev16(cs.lut), dev16(sc), dev16(of)
+    rcodes = None
+    if relayout:
+        rcodes = any4.any4_repack(codes_dev, bits)
+        assert np.array_equal(host_u32(rcodes), oracle.repack(packed, K, bits)), (shape_name, "re-laid-out words")
+    # dequantised weights, bit for bit, from ONE launch on the whole matrix
+    w = any4.any4_dequant(codes_dev, lut, scale, offset, K, bits, group=group)
+    torch.cuda.synchronize()
+    bands = [(0, N)] if N * K <= DEQUANT_WHOLE_LIMIT else [(0, 16), (N - 4096, N)]
+    for r0, r1 in bands:
+        w_ref = oracle.dequant(packed[r0:r1], cs.lut[r0:r1], sc[r0:r1], of[r0:r1], K, bits, group=group, f16=f16)
+        assert np.array_equal(w[r0:r1].cpu().numpy().view(np.uint32), w_ref.view(np.uint32)), (shape_name, "dequant", r0, r1)
+        del w_ref
+    del w
+    torch.cuda.empty_cache()
     rng = np.random.default_rng(seed + 1)
-    rows = np.unique(np.concatenate([[0, 1, N - 2, N - 1], rng.integers(0, N, SAMPLE_ROWS)]))
-    packed_rows = oracle.pack(cs.codes_u8[rows], bits)
-    assert np.array_equal(host_u32(codes_dev[torch.from_numpy(rows).cuda()]), packed_rows)
-    # dequant of the sampled rows, bit-exact, through a call on the whole matrix slice by slice
-    w_ref = oracle.dequant(packed_rows, cs.lut[rows], cs.scale[rows], cs.offset[rows], K, bits)
-    idx = torch.from_numpy(rows).cuda()
-    w = any4.any4_dequant(codes_dev[idx].contiguous(), lut[idx].contiguous(), scale[idx].contiguous(),
-                          offset[idx].contiguous(), K, bits)
-    assert np.array_equal(w.cpu().numpy().view(np.uint32), w_ref.view(np.uint32))
-    worst = 0.0
     for M in Ms:
         x = cs.x[:M]
-        y64 = oracle.gemm(x, packed_rows, cs.lut[rows], cs.scale[rows], cs.offset[rows], K, bits, threads=8)
-        y = any4.any4_gemm(dev_bf16(x), codes_dev, lut, scale, offset, bits)
-        y_re = any4.any4_gemm_repacked(dev_bf16(x), rcodes, lut, scale, offset, bits)
+        y = any4.any4_gemm(dev16(x), codes_dev, lut, scale, offset, bits, group=group)
         torch.cuda.synchronize()
-        assert torch.equal(y.view(torch.int16), y_re.view(torch.int16)), (shape_name, M, "re-laid-out codes")
-        worst = max(worst, check_gemm(y[:, idx], y64, oracle.rms(y64), (shape_name, M, N, K, bits)))
-    return worst
+        if rcodes is not None:
+            y_re = any4.any4_gemm_repacked(dev16(x), rcodes, lut, scale, offset, bits)
+            torch.cuda.synchronize()
+            assert torch.equal(y.view(torch.int16), y_re.view(torch.int16)), (shape_name, M, "re-laid-out codes")
+        if M <= 16:
+            cols = None
+            y64 = oracle.gemm(x, packed, cs.lut, sc, of, K, bits, threads=ORACLE_THREADS, group=group, f16=f16)
+            got = y.float().cpu().numpy().astype(np.float64)
+        else:
+            cols = prefill_columns(N, rng)
+            y64 = oracle.gemm(x, packed[cols], cs.lut[cols], sc[cols], of[cols], K, bits, threads=ORACLE_THREADS,
+                              group=group, f16=f16)
+            got = y[:, torch.from_numpy(cols).cuda()].float().cpu().numpy().astype(np.float64)
+        assert got.shape == y64.shape
+        gemm_tolerance_check(got, y64, oracle.rms(y64), half_ulp, (shape_name, M, N, K, bits, group, f16))
 
 
 @pytest.mark.parametrize("name", list(inputs.LLAMA3_8B_SHAPES))
 def test_llama3_8b_decode_and_prefill_shapes(any4, oracle, name):
-    """Configs 2 and 4: M = 1, 8 (decode) and M = 2048 (prefill) on the 8B linears."""
+    """Configs 2 and 4: M = 1, 8 (decode, every output) and M = 2048 (prefill, every n-block) on the 8B linears."""
     N, K = inputs.LLAMA3_8B_SHAPES[name]
     i = list(inputs.LLAMA3_8B_SHAPES).index(name)
-    sampled_rows_check(any4, oracle, name, N, K, 4, (1, 8, 2048), seed=inputs.case_seed(20, i))
+    full_shape_check(any4, oracle, name, N, K, 4, (1, 8, 2048), seed=inputs.case_seed(20, i))
 
 
 @pytest.mark.parametrize("variant", ("group64", "group1024", "f16"))
 @pytest.mark.parametrize("name", list(inputs.LLAMA3_8B_SHAPES))
 def test_llama3_8b_shapes_other_groups_and_fp16(any4, oracle, name, variant):
-    """The full 8B linears at M = 1, 8 and 2048 with groups of 64 / 1024 weights and with fp16 storage:
-    sampled output columns against the oracle."""
+    """The full 8B linears at M = 1, 8 and 2048 with groups of 64 / 1024 weights and with fp16 storage."""
     N, K = inputs.LLAMA3_8B_SHAPES[name]
     i = list(inputs.LLAMA3_8B_SHAPES).index(name)
-    seed = inputs.case_seed(60, i, len(variant))
-    f16 = variant == "f16"
     group = {"group64": 64, "group1024": 1024, "f16": 128}[variant]
     if K % group:
         pytest.skip("the group must divide K")
-    Ms = (1, 8, 2048)
-    cs = inputs.make_case(max(Ms), N, K, 4, seed, f16=f16)
-    if group == 64:
-        other = inputs.make_case(1, N, K, 4, seed + 1000)
-        sc = np.ascontiguousarray(np.stack([cs.scale, other.scale], axis=2).reshape(N, -1))
-        of = np.ascontiguousarray(np.stack([cs.offset, other.offset], axis=2).reshape(N, -1))
-    else:
-        sc, of = np.ascontiguousarray(cs.scale[:, ::group // 128]), np.ascontiguousarray(cs.offset[:, ::group // 128])
-    dev = dev_f16 if f16 else dev_bf16
-    codes_dev = any4.any4_pack(torch.from_numpy(cs.codes_u8).cuda(), 4)
-    lut_d, sc_d, of_d = dev(cs.lut), dev(sc), dev(of)
-    rng = np.random.default_rng(seed + 1)
-    rows = np.unique(np.concatenate([[0, 1, N - 2, N - 1], rng.integers(0, N, SAMPLE_ROWS)]))
-    idx = torch.from_numpy(rows).cuda()
-    packed_rows = oracle.pack(cs.codes_u8[rows], 4)
-    for M in Ms:
-        x = cs.x[:M]
-        y64 = oracle.gemm(x, packed_rows, cs.lut[rows], sc[rows], of[rows], K, 4, threads=8, group=group, f16=f16)
-        y = any4.any4_gemm(dev(x), codes_dev, lut_d, sc_d, of_d, 4, group=group)
-        torch.cuda.synchronize()
-        got = y[:, idx].float().cpu().numpy().astype(np.float64)
-        rms = oracle.rms(y64)
-        tol = 1e-2 * rms + np.abs(y64) * (2.0 ** -11 if f16 else 2.0 ** -8)
-        assert np.all(np.abs(got - y64) <= tol), (name, variant, M, float(np.abs(got - y64).max()), rms)
+    full_shape_check(any4, oracle, name, N, K, 4, (1, 8, 2048), seed=inputs.case_seed(60, i, len(variant)),
+                     group=group, f16=variant == "f16", relayout=False)
 
 
 @pytest.mark.parametrize("name", list(inputs.LLAMA3_70B_SHAPES))
 def test_llama3_70b_batch_sweep(any4, oracle, name):
-    """Config 3: M in {1, 2, 4, 8, 16} on the 70B linears."""
+    """Config 3: M in {1, 2, 4, 8, 16} on the 70B linears, every output."""
     N, K = inputs.LLAMA3_70B_SHAPES[name]
     i = list(inputs.LLAMA3_70B_SHAPES).index(name)
-    sampled_rows_check(any4, oracle, name, N, K, 4, (1, 2, 4, 8, 16), seed=inputs.case_seed(30, i))
+    full_shape_check(any4, oracle, name, N, K, 4, (1, 2, 4, 8, 16), seed=inputs.case_seed(30, i))
 
 
 @pytest.mark.parametrize("bits", (3, 2))
 @pytest.mark.parametrize("name", list(inputs.LLAMA3_70B_SHAPES))
 def test_llama3_70b_any3_any2(any4, oracle, name, bits):
-    """Config 5: 3- and 2-bit variants at M = 1 and 16 on the 70B linears."""
+    """Config 5: 3- and 2-bit variants at M = 1 and 16 on the 70B linears, every output."""
     N, K = inputs.LLAMA3_70B_SHAPES[name]
     i = list(inputs.LLAMA3_70B_SHAPES).index(name)
-    sampled_rows_check(any4, oracle, name, N, K, bits, (1, 16), seed=inputs.case_seed(50 + bits, i))
+    full_shape_check(any4, oracle, name, N, K, bits, (1, 16), seed=inputs.case_seed(50 + bits, i))
