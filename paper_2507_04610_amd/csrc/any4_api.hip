@@ -135,7 +135,12 @@ int gemm_dispatch(const uint16_t* x, const uint32_t* codes, bool repacked, const
     if (plan.workspace > 0 && (!workspace || workspace_bytes < plan.workspace)) return ANY4_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t e;
-    if (lr < 0 && plan.stream && !plan.chunked) {
+    // one to four rows of x, a table, groups of 128, bf16: the packed-activation kernel (whole K in one
+    // block, no workspace) where it takes the shape
+    const PackPlan pk = (M <= 4 && lut && lr == 0 && !f16) ? plan_pack(M, N, K, bits, device_compute_units()) : PackPlan{};
+    if (pk.ok) {
+        e = launch_decode_pack(x, codes, lut, scale, offset, M, N, K, bits, repacked, pk, y, s);
+    } else if (lr < 0 && plan.stream && !plan.chunked) {
         // groups of 64 weights, M <= 16: the streaming kernel takes 8 rows of x a launch
         e = hipSuccess;
         for (int64_t m0 = 0; m0 < M && e == hipSuccess; m0 += kFineRows) {

@@ -1,0 +1,11 @@
+// The 4-bit variants of the packed-activation kernel (a translation unit per code width keeps the
+// build parallel).
+#include "any4_decode_pack.h"
+
+namespace any4 {
+
+hipError_t launch_pack_bits4(const pack::Params& p, const PackPlan& pl, bool repacked, hipStream_t stream) {
+    return repacked ? launch_pack_b<4, true>(p, pl, stream) : launch_pack_b<4, false>(p, pl, stream);
+}
+
+}  // namespace any4

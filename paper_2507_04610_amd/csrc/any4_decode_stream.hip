@@ -871,7 +871,10 @@ StreamPlan plan_stream(int64_t M, int64_t N, int64_t K, int cus) {
         if (sgroups > slab_max) continue;
         slabs = (G + sgroups - 1) / sgroups;
         if (slabs > kMaxSplit) continue;
-        int bps = cus / slabs;
+#ifndef ANY4_BPC
+#define ANY4_BPC 1
+#endif
+        int bps = cus * ANY4_BPC / slabs;
         if (bps < 1) bps = 1;
         if (bps > tiles) bps = (int)tiles;
         const int64_t tpb = (tiles + bps - 1) / bps;

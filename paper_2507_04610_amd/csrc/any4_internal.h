@@ -34,6 +34,21 @@ template <auto Kern> hipError_t ensure_lds(int bytes) {
     return e;
 }
 
+// Work split of the packed-activation kernel for M <= 4 (any4_decode_pack.hip): the whole K axis in one
+// block, no workspace.
+struct PackPlan {
+    bool ok;              // the kernel takes this problem
+    int mp;               // rows of x rounded up to 1, 2 or 4
+    int passes;           // units of 4 groups per wavefront and tile
+    int64_t tiles;        // 16-row tiles
+    int nblocks;          // grid size
+};
+PackPlan plan_pack(int64_t M, int64_t N, int64_t K, int bits, int cus);
+hipError_t launch_decode_pack(const uint16_t* x, const uint32_t* codes, const uint16_t* lut,
+                              const uint16_t* scale, const uint16_t* offset, int64_t M, int64_t N,
+                              int64_t K, int bits, bool repacked, const PackPlan& pl, uint16_t* y,
+                              hipStream_t stream);
+
 // How any4_gemm runs a given problem; a pure function of (M, N, K, bits) so that
 // any4_gemm_workspace_bytes() and any4_gemm() always agree.
 struct GemmPlan {
