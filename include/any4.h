@@ -150,6 +150,23 @@ int any4_gemm_grouped(const uint16_t* x, const uint32_t* codes, const uint16_t* 
                       uint16_t* y, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * any4_dequant_single_table / any4_gemm_single_table - the same two operations for formats that keep
+ * ONE table for the whole matrix instead of one per row (the paper's nf4 and af4 comparisons: section
+ * 2.4.1, last paragraph; section 5, "Speed Comparisons"): lut1 is bf16 [1][2^bits] and serves every
+ * row, w[n][k] = lut1[code[n][k]] * scale[n][k/128] + offset[n][k/128].  The kernels build their lookup
+ * structure from it once per block (not once per 16 rows) and read no per-row tables; everything else
+ * - groups of 128, bf16, plain code layout, shapes, alignment, workspace (any4_gemm_workspace_bytes),
+ * error behaviour - is that of any4_dequant / any4_gemm, and so is the result: the same bits as with lut1
+ * repeated N times.  lut1 must not be NULL.
+ */
+int any4_dequant_single_table(const uint32_t* codes, const uint16_t* lut1, const uint16_t* scale,
+                              const uint16_t* offset, int64_t N, int64_t K, int bits, float* w, void* stream);
+int any4_gemm_single_table(const uint16_t* x, const uint32_t* codes, const uint16_t* lut1,
+                           const uint16_t* scale, const uint16_t* offset,
+                           int64_t M, int64_t N, int64_t K, int bits,
+                           uint16_t* y, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * any4_repack - re-arrange packed codes offline into the order the kernels read them in.
  * The paper stores the weights in the operand order of the matrix instruction so that a lane's
  * load needs no shuffling (section 4.2, second paragraph).  On this GPU the row-major layout

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_PKG, "libany4.so")
 GROUP = 128
 
 EXPORTS = ("any4_pack", "any4_dequant", "any4_gemm", "any4_gemm_workspace_bytes", "any4_repack", "any4_repack_bytes", "any4_gemm_repacked", "any4_dequant_grouped", "any4_gemm_grouped", "any4_dequant_f16", "any4_gemm_f16",
-           "any4_quantize", "any4_quantize_max_k", "any4_gemm_noalloc", "any4_strerror", "any4_version")
+           "any4_quantize", "any4_quantize_max_k", "any4_gemm_noalloc", "any4_dequant_single_table", "any4_gemm_single_table", "any4_strerror", "any4_version")
 
 
 class Any4Error(RuntimeError):
@@ -56,6 +56,10 @@ def load_library() -> ctypes.CDLL:
     lib.any4_gemm_grouped.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, ci, ci, vp, vp, ctypes.c_size_t, vp]
     lib.any4_gemm_repacked.restype = ci
     lib.any4_gemm_repacked.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, ci, vp, vp, ctypes.c_size_t, vp]
+    lib.any4_dequant_single_table.restype = ci
+    lib.any4_dequant_single_table.argtypes = [vp, vp, vp, vp, i64, i64, ci, vp, vp]
+    lib.any4_gemm_single_table.restype = ci
+    lib.any4_gemm_single_table.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, ci, vp, vp, ctypes.c_size_t, vp]
     lib.any4_gemm_noalloc.restype = ci
     lib.any4_gemm_noalloc.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, ci, vp, vp]
     lib.any4_repack.restype = ci
@@ -94,7 +98,7 @@ def _shape(t: torch.Tensor, want, name: str) -> None:
         raise Any4Error(f"{name} must have shape {tuple(want)}, got {tuple(t.shape)}")
 
 
-def _check_quant_shapes(codes, lut, scale, offset, N, K, bits, group, repacked=False) -> None:
+def _check_quant_shapes(codes, lut, scale, offset, N, K, bits, group, repacked=False, single_table=False) -> None:
     """the kernels index these arrays from (N, K, bits, group) alone: a wrong shape would make them read
     out of bounds on the device, so it is refused here"""
     if bits not in (4, 3, 2):
@@ -107,7 +111,7 @@ def _check_quant_shapes(codes, lut, scale, offset, N, K, bits, group, repacked=F
             raise Any4Error(f"rcodes must hold {need} words (any4_repack_bytes), got {codes.numel()}")
     else:
         _shape(codes, (N, row_words(K, bits)), "codes")
-    if lut is not None:
+    if lut is not None and not (single_table and tuple(lut.shape) == (1, 1 << bits)):
         _shape(lut, (N, 1 << bits), "lut")
     _shape(scale, (N, K // group), "scale")
     _shape(offset, (N, K // group), "offset")
@@ -149,14 +153,16 @@ def any4_pack(codes_u8: torch.Tensor, bits: int = 4, out: torch.Tensor | None = 
 
 def any4_dequant(codes: torch.Tensor, lut: torch.Tensor | None, scale: torch.Tensor, offset: torch.Tensor,
                  K: int, bits: int = 4, out: torch.Tensor | None = None, group: int = GROUP) -> torch.Tensor:
-    """fp32 [N,K] dequantised weights (lut None with bits 4: the int4 grid, value = code - 8);
+    """fp32 [N,K] dequantised weights (lut None with bits 4: the int4 grid, value = code - 8; lut of
+    shape [1, 2^bits]: one table for the whole matrix);
     scale / offset are [N, K / group] (any4_dequant_grouped when group is not 128).
     lut / scale / offset are bf16, or all fp16 (any4_dequant_f16: groups of 128, a table)."""
     lib = load_library()
     N = codes.shape[0]
     pc = _dev(codes, torch.int32, "codes")
     dt = scale.dtype if isinstance(scale, torch.Tensor) and scale.dtype == torch.float16 else torch.bfloat16
-    _check_quant_shapes(codes, lut, scale, offset, N, K, bits, group)
+    single = lut is not None and N != 1 and tuple(lut.shape) == (1, 1 << bits)
+    _check_quant_shapes(codes, lut, scale, offset, N, K, bits, group, single_table=single)
     pl = _dev(lut, dt, "lut") if lut is not None else None
     ps = _dev(scale, dt, "scale")
     po = _dev(offset, dt, "offset")
@@ -164,7 +170,11 @@ def any4_dequant(codes: torch.Tensor, lut: torch.Tensor | None, scale: torch.Ten
         out = torch.empty((N, K), dtype=torch.float32, device=codes.device)
     _shape(out, (N, K), "out")
     pw = _dev(out, torch.float32, "out")
-    if dt == torch.float16:
+    if single:
+        if dt == torch.float16 or group != GROUP:
+            raise Any4Error("one table for the whole matrix comes with bf16 and groups of 128")
+        _check(lib.any4_dequant_single_table(pc, pl, ps, po, N, K, bits, pw, _stream()), "any4_dequant_single_table")
+    elif dt == torch.float16:
         if group != GROUP:
             raise Any4Error("fp16 inputs come with groups of 128")
         _check(lib.any4_dequant_f16(pc, pl, ps, po, N, K, bits, pw, _stream()), "any4_dequant_f16")
@@ -185,8 +195,14 @@ def _gemm(entry: str, x, codes, N, lut, scale, offset, bits, out, workspace, gro
         entry = "any4_gemm_f16"
     px = _dev(x, dt, "x")
     pc = _dev(codes, torch.int32, "codes")
+    # a table of ONE row for a matrix of several: the single-table formats (any4_gemm_single_table)
+    single = lut is not None and N != 1 and tuple(lut.shape) == (1, 1 << bits)
+    if single:
+        if entry != "any4_gemm":
+            raise Any4Error("one table for the whole matrix comes with bf16, groups of 128 and the plain code layout")
+        entry = "any4_gemm_single_table"
     _check_quant_shapes(codes, lut, scale, offset, N, K, bits, GROUP if group is None else group,
-                        repacked=entry == "any4_gemm_repacked")
+                        repacked=entry == "any4_gemm_repacked", single_table=single)
     pl = _dev(lut, dt, "lut") if lut is not None else None
     ps = _dev(scale, dt, "scale")
     po = _dev(offset, dt, "offset")
@@ -210,7 +226,8 @@ def any4_gemm(x: torch.Tensor, codes: torch.Tensor, lut: torch.Tensor | None, sc
               offset: torch.Tensor, bits: int = 4, out: torch.Tensor | None = None,
               workspace: torch.Tensor | None = None, group: int = GROUP) -> torch.Tensor:
     """bf16 [M,N] = x[M,K] . dequant(codes, lut, scale, offset)[N,K]^T
-    (lut None with bits 4: the int4 grid, value = code - 8, run without a table);
+    (lut None with bits 4: the int4 grid, value = code - 8, run without a table; lut of shape
+    [1, 2^bits]: one table for the whole matrix, any4_gemm_single_table);
     scale / offset are [N, K / group] (any4_gemm_grouped when group is not 128).
     With x, lut, scale, offset all fp16 the result is fp16 (any4_gemm_f16: groups of 128, a table)."""
     if group == GROUP:

@@ -115,11 +115,11 @@ using namespace any4;
 namespace any4 {
 
 int gemm_dispatch(const uint16_t* x, const uint32_t* codes, bool repacked, const uint16_t* lut,
-                           const uint16_t* scale, const uint16_t* offset, int64_t M, int64_t N, int64_t K,
-                           int bits, int group, uint16_t* y, void* workspace, size_t workspace_bytes, void* stream,
-                           bool f16) {
+                  const uint16_t* scale, const uint16_t* offset, int64_t M, int64_t N, int64_t K,
+                  int bits, int group, uint16_t* y, void* workspace, size_t workspace_bytes, void* stream,
+                  bool f16, bool one_table) {
     if (!x || !codes || !scale || !offset || !y) return ANY4_ERR_NULL;
-    if (f16 && !lut) return ANY4_ERR_NULL;                           // fp16: table-based only
+    if ((f16 || one_table) && !lut) return ANY4_ERR_NULL;            // fp16 / one table for all rows: a table is required
     if (!lut && (bits != 4 || repacked)) return ANY4_ERR_NULL;       // no table = the 4-bit integer grid, plain layout only
     if (int rc = shape_check(N, K, bits)) return rc;
     if (M < 1) return ANY4_ERR_SHAPE;
@@ -137,33 +137,33 @@ int gemm_dispatch(const uint16_t* x, const uint32_t* codes, bool repacked, const
     hipError_t e;
     // one to four rows of x, a table, groups of 128, bf16: the packed-activation kernel (whole K in one
     // block, no workspace) where it takes the shape
-    const PackPlan pk = (M <= 4 && lut && lr == 0 && !f16) ? plan_pack(M, N, K, bits, device_compute_units()) : PackPlan{};
+    const PackPlan pk = (M <= 4 && lut && lr == 0 && !f16) ? plan_pack(M, N, K, bits, one_table, device_compute_units()) : PackPlan{};
     if (pk.ok) {
-        e = launch_decode_pack(x, codes, lut, scale, offset, M, N, K, bits, repacked, pk, y, s);
+        e = launch_decode_pack(x, codes, lut, scale, offset, M, N, K, bits, repacked, one_table, pk, y, s);
     } else if (lr < 0 && plan.stream && !plan.chunked) {
         // groups of 64 weights, M <= 16: the streaming kernel takes 8 rows of x a launch
         e = hipSuccess;
         for (int64_t m0 = 0; m0 < M && e == hipSuccess; m0 += kFineRows) {
             const int64_t rows = M - m0 < kFineRows ? M - m0 : kFineRows;
-            e = launch_decode_stream(x + m0 * K, codes, lut, scale, offset, rows, N, K, bits, lr, false, false, plan.sp,
+            e = launch_decode_stream(x + m0 * K, codes, lut, scale, offset, rows, N, K, bits, lr, false, false, one_table, plan.sp,
                                      y + m0 * N, workspace, s);
         }
     } else if (lr < 0) {
-        e = launch_prefill(x, codes, lut, scale, offset, M, N, K, bits, lr, false, false, device_compute_units(), y, workspace, s);
+        e = launch_prefill(x, codes, lut, scale, offset, M, N, K, bits, lr, false, false, one_table, device_compute_units(), y, workspace, s);
     } else if (plan.chunked) {
         // launches run one after the other on the stream and leave the workspace's counters clean
         e = hipSuccess;
         for (int64_t m0 = 0; m0 < M && e == hipSuccess; m0 += kStreamMaxM) {
             const int64_t rows = M - m0 < kStreamMaxM ? M - m0 : kStreamMaxM;
-            e = launch_decode_stream(x + m0 * K, codes, lut, scale, offset, rows, N, K, bits, lr, repacked, f16,
+            e = launch_decode_stream(x + m0 * K, codes, lut, scale, offset, rows, N, K, bits, lr, repacked, f16, one_table,
                                      rows == kStreamMaxM ? plan.sp : plan.sp_tail, y + m0 * N, workspace, s);
         }
     } else if (plan.stream) {
-        e = launch_decode_stream(x, codes, lut, scale, offset, M, N, K, bits, lr, repacked, f16, plan.sp, y, workspace, s);
+        e = launch_decode_stream(x, codes, lut, scale, offset, M, N, K, bits, lr, repacked, f16, one_table, plan.sp, y, workspace, s);
     } else if (plan.decode) {
-        e = launch_decode(x, codes, lut, scale, offset, M, N, K, bits, plan, y, static_cast<float*>(workspace), s);
+        e = launch_decode(x, codes, lut, scale, offset, M, N, K, bits, plan, one_table, y, static_cast<float*>(workspace), s);
     } else {
-        e = launch_prefill(x, codes, lut, scale, offset, M, N, K, bits, lr, repacked, f16, device_compute_units(), y, workspace, s);
+        e = launch_prefill(x, codes, lut, scale, offset, M, N, K, bits, lr, repacked, f16, one_table, device_compute_units(), y, workspace, s);
     }
     return e == hipSuccess ? ANY4_OK : ANY4_ERR_HIP;
 }
@@ -180,18 +180,30 @@ int any4_pack(const uint8_t* codes_u8, int64_t N, int64_t K, int bits, uint32_t*
                ? ANY4_OK : ANY4_ERR_HIP;
 }
 
-int any4_dequant_grouped(const uint32_t* codes, const uint16_t* lut, const uint16_t* scale,
-                         const uint16_t* offset, int64_t N, int64_t K, int bits, int group, float* w,
-                         void* stream) {
+static int dequant_any(const uint32_t* codes, const uint16_t* lut, bool one_table, const uint16_t* scale,
+                       const uint16_t* offset, int64_t N, int64_t K, int bits, int group, float* w,
+                       void* stream) {
     if (!codes || !scale || !offset || !w) return ANY4_ERR_NULL;
+    if (one_table && !lut) return ANY4_ERR_NULL;
     if (!lut && bits != 4) return ANY4_ERR_NULL;           // no table = the 4-bit integer grid only
     if (int rc = shape_check(N, K, bits)) return rc;
     int lr;
     if (!group_shift(K, group, &lr)) return ANY4_ERR_SHAPE;
     if (!aligned16(codes) || !aligned16(lut) || !aligned16(scale) || !aligned16(offset) || !aligned16(w))
         return ANY4_ERR_ALIGN;
-    return launch_dequant(codes, lut, scale, offset, N, K, bits, lr, false, w, static_cast<hipStream_t>(stream)) == hipSuccess
+    return launch_dequant(codes, lut, scale, offset, N, K, bits, lr, false, one_table, w, static_cast<hipStream_t>(stream)) == hipSuccess
                ? ANY4_OK : ANY4_ERR_HIP;
+}
+
+int any4_dequant_grouped(const uint32_t* codes, const uint16_t* lut, const uint16_t* scale,
+                         const uint16_t* offset, int64_t N, int64_t K, int bits, int group, float* w,
+                         void* stream) {
+    return dequant_any(codes, lut, false, scale, offset, N, K, bits, group, w, stream);
+}
+
+int any4_dequant_single_table(const uint32_t* codes, const uint16_t* lut1, const uint16_t* scale,
+                              const uint16_t* offset, int64_t N, int64_t K, int bits, float* w, void* stream) {
+    return dequant_any(codes, lut1, true, scale, offset, N, K, bits, ANY4_GROUP, w, stream);
 }
 
 int any4_dequant_f16(const uint32_t* codes, const uint16_t* lut, const uint16_t* scale,
@@ -200,7 +212,7 @@ int any4_dequant_f16(const uint32_t* codes, const uint16_t* lut, const uint16_t*
     if (int rc = shape_check(N, K, bits)) return rc;
     if (!aligned16(codes) || !aligned16(lut) || !aligned16(scale) || !aligned16(offset) || !aligned16(w))
         return ANY4_ERR_ALIGN;
-    return launch_dequant(codes, lut, scale, offset, N, K, bits, 0, true, w, static_cast<hipStream_t>(stream)) == hipSuccess
+    return launch_dequant(codes, lut, scale, offset, N, K, bits, 0, true, false, w, static_cast<hipStream_t>(stream)) == hipSuccess
                ? ANY4_OK : ANY4_ERR_HIP;
 }
 
@@ -233,25 +245,31 @@ size_t any4_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int bits) {
 int any4_gemm(const uint16_t* x, const uint32_t* codes, const uint16_t* lut, const uint16_t* scale,
               const uint16_t* offset, int64_t M, int64_t N, int64_t K, int bits, uint16_t* y,
               void* workspace, size_t workspace_bytes, void* stream) {
-    return gemm_dispatch(x, codes, false, lut, scale, offset, M, N, K, bits, ANY4_GROUP, y, workspace, workspace_bytes, stream, false);
+    return gemm_dispatch(x, codes, false, lut, scale, offset, M, N, K, bits, ANY4_GROUP, y, workspace, workspace_bytes, stream, false, false);
 }
 
 int any4_gemm_f16(const uint16_t* x, const uint32_t* codes, const uint16_t* lut, const uint16_t* scale,
                   const uint16_t* offset, int64_t M, int64_t N, int64_t K, int bits, uint16_t* y,
                   void* workspace, size_t workspace_bytes, void* stream) {
-    return gemm_dispatch(x, codes, false, lut, scale, offset, M, N, K, bits, ANY4_GROUP, y, workspace, workspace_bytes, stream, true);
+    return gemm_dispatch(x, codes, false, lut, scale, offset, M, N, K, bits, ANY4_GROUP, y, workspace, workspace_bytes, stream, true, false);
 }
 
 int any4_gemm_grouped(const uint16_t* x, const uint32_t* codes, const uint16_t* lut, const uint16_t* scale,
                       const uint16_t* offset, int64_t M, int64_t N, int64_t K, int bits, int group, uint16_t* y,
                       void* workspace, size_t workspace_bytes, void* stream) {
-    return gemm_dispatch(x, codes, false, lut, scale, offset, M, N, K, bits, group, y, workspace, workspace_bytes, stream, false);
+    return gemm_dispatch(x, codes, false, lut, scale, offset, M, N, K, bits, group, y, workspace, workspace_bytes, stream, false, false);
 }
 
 int any4_gemm_repacked(const uint16_t* x, const uint32_t* rcodes, const uint16_t* lut, const uint16_t* scale,
                        const uint16_t* offset, int64_t M, int64_t N, int64_t K, int bits, uint16_t* y,
                        void* workspace, size_t workspace_bytes, void* stream) {
-    return gemm_dispatch(x, rcodes, true, lut, scale, offset, M, N, K, bits, ANY4_GROUP, y, workspace, workspace_bytes, stream, false);
+    return gemm_dispatch(x, rcodes, true, lut, scale, offset, M, N, K, bits, ANY4_GROUP, y, workspace, workspace_bytes, stream, false, false);
+}
+
+int any4_gemm_single_table(const uint16_t* x, const uint32_t* codes, const uint16_t* lut1, const uint16_t* scale,
+                           const uint16_t* offset, int64_t M, int64_t N, int64_t K, int bits, uint16_t* y,
+                           void* workspace, size_t workspace_bytes, void* stream) {
+    return gemm_dispatch(x, codes, false, lut1, scale, offset, M, N, K, bits, ANY4_GROUP, y, workspace, workspace_bytes, stream, false, true);
 }
 
 size_t any4_repack_bytes(int64_t N, int64_t K, int bits) {

@@ -29,7 +29,7 @@ template <int BITS, int MT>
 __global__ __launch_bounds__(kDecodeWaves * 64) void decode_rows_kernel(
     const uint16_t* __restrict__ x, const uint32_t* __restrict__ codes,
     const uint16_t* __restrict__ lut, const uint16_t* __restrict__ scale,
-    const uint16_t* __restrict__ offset, int M, int64_t N, int64_t K, int ksplit,
+    const uint16_t* __restrict__ offset, int M, int64_t N, int64_t K, int ksplit, int one_table,
     uint16_t* __restrict__ y, float* __restrict__ partial) {
     constexpr int L = 1 << BITS;
     constexpr uint32_t mask = L - 1;
@@ -43,7 +43,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64) void decode_rows_kernel(
     const bool active = n < N;                      // whole wave takes the same branch
     const int64_t nn = active ? n : 0;
 
-    if (lane < L) table[wave][lane] = lut ? bf16_to_f32(lut[nn * L + lane]) : (float)(lane - L / 2);   // no table: the integer grid
+    if (lane < L) table[wave][lane] = lut ? bf16_to_f32(lut[(one_table ? 0 : nn * L) + lane]) : (float)(lane - L / 2);   // no table: the integer grid
     __syncthreads();                                // one barrier, reached by every wave
     if (!active) return;
 
@@ -127,7 +127,7 @@ hipError_t launch_reduce_slices(const float* partial, int ksplit, int64_t MN, ui
 template <int BITS>
 static hipError_t launch_decode_bits(const uint16_t* x, const uint32_t* codes, const uint16_t* lut,
                                      const uint16_t* scale, const uint16_t* offset, int M, int64_t N,
-                                     int64_t K, const GemmPlan& plan, uint16_t* y, float* partial,
+                                     int64_t K, const GemmPlan& plan, bool one_table, uint16_t* y, float* partial,
                                      hipStream_t stream) {
     const int64_t tasks = N * plan.ksplit;
     const int64_t blocks = (tasks + kDecodeWaves - 1) / kDecodeWaves;
@@ -135,7 +135,7 @@ static hipError_t launch_decode_bits(const uint16_t* x, const uint32_t* codes, c
     const dim3 grid((unsigned)blocks), block(kDecodeWaves * 64);
 #define ANY4_LAUNCH(MT)                                                                         \
     hipLaunchKernelGGL((decode_rows_kernel<BITS, MT>), grid, block, 0, stream, x, codes, lut,   \
-                       scale, offset, M, N, K, plan.ksplit, y, partial)
+                       scale, offset, M, N, K, plan.ksplit, one_table ? 1 : 0, y, partial)
     if (M == 1) ANY4_LAUNCH(1);
     else if (M == 2) ANY4_LAUNCH(2);
     else if (M <= 4) ANY4_LAUNCH(4);
@@ -152,12 +152,12 @@ static hipError_t launch_decode_bits(const uint16_t* x, const uint32_t* codes, c
 
 hipError_t launch_decode(const uint16_t* x, const uint32_t* codes, const uint16_t* lut,
                          const uint16_t* scale, const uint16_t* offset,
-                         int64_t M, int64_t N, int64_t K, int bits, const GemmPlan& plan,
+                         int64_t M, int64_t N, int64_t K, int bits, const GemmPlan& plan, bool one_table,
                          uint16_t* y, float* partial, hipStream_t stream) {
     switch (bits) {
-        case 4: return launch_decode_bits<4>(x, codes, lut, scale, offset, (int)M, N, K, plan, y, partial, stream);
-        case 3: return launch_decode_bits<3>(x, codes, lut, scale, offset, (int)M, N, K, plan, y, partial, stream);
-        default: return launch_decode_bits<2>(x, codes, lut, scale, offset, (int)M, N, K, plan, y, partial, stream);
+        case 4: return launch_decode_bits<4>(x, codes, lut, scale, offset, (int)M, N, K, plan, one_table, y, partial, stream);
+        case 3: return launch_decode_bits<3>(x, codes, lut, scale, offset, (int)M, N, K, plan, one_table, y, partial, stream);
+        default: return launch_decode_bits<2>(x, codes, lut, scale, offset, (int)M, N, K, plan, one_table, y, partial, stream);
     }
 }
 

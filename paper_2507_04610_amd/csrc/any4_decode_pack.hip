@@ -5,7 +5,7 @@
 namespace any4 {
 
 // Whether and how the packed-activation kernel takes a problem; a pure function of its arguments.
-PackPlan plan_pack(int64_t M, int64_t N, int64_t K, int bits, int cus) {
+PackPlan plan_pack(int64_t M, int64_t N, int64_t K, int bits, bool one_table, int cus) {
     PackPlan pl{};
     const int64_t G = K / kGroup;
     const int64_t tiles = (N + pack::kTile - 1) / pack::kTile;
@@ -34,7 +34,7 @@ PackPlan plan_pack(int64_t M, int64_t N, int64_t K, int bits, int cus) {
 
 hipError_t launch_decode_pack(const uint16_t* x, const uint32_t* codes, const uint16_t* lut,
                               const uint16_t* scale, const uint16_t* offset, int64_t M, int64_t N,
-                              int64_t K, int bits, bool repacked, const PackPlan& pl, uint16_t* y,
+                              int64_t K, int bits, bool repacked, bool one_table, const PackPlan& pl, uint16_t* y,
                               hipStream_t stream) {
     if (!pl.ok || !lut) return hipErrorInvalidValue;
     pack::Params p{};
@@ -44,7 +44,8 @@ hipError_t launch_decode_pack(const uint16_t* x, const uint32_t* codes, const ui
     p.nblocks = pl.nblocks;
     p.tpb = (int)(pl.tiles / pl.nblocks); p.trem = (int)(pl.tiles % pl.nblocks);
     p.codes_bytes = (int)((repacked ? pl.tiles * pack::kTile : N) * (K * bits / 8));
-    p.lut_bytes = (int)(N * (2 << bits));
+    p.lut_bytes = (int)((one_table ? 1 : N) * (2 << bits));
+    p.one_table = one_table ? 1 : 0;
     p.so_bytes = (int)(N * (K / kGroup) * 2);
     if (bits == 4) return launch_pack_bits4(p, pl, repacked, stream);
     if (bits == 3) return launch_pack_bits3(p, pl, repacked, stream);

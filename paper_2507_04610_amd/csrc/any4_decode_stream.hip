@@ -114,6 +114,7 @@ struct Params {
                                      // of its row (rows of G >> lr entries)
     int slabs, slab_groups;          // groups per slab (the last slab may have fewer)
     int blocks_per_slab, tiles;
+    int one_table;                   // lut holds ONE row that serves every row of the matrix (built once per block)
 };
 
 // LDS barrier that does not wait for outstanding global loads (the prefetched codes stay in flight)
@@ -197,7 +198,9 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
     const int nc = min(n, (int)(N - 1 - (int64_t)last_tile * kTile));        // this lane's row inside the last tile
     const uint32_t row_bytes = (uint32_t)(K * BITS / 8);
     const uint32_t vc_norm = (uint32_t)n * row_bytes + (uint32_t)q * QB, vc_last = (uint32_t)nc * row_bytes + (uint32_t)q * QB;
-    const uint32_t vl_norm = (uint32_t)n * LUTB, vl_last = (uint32_t)nc * LUTB;
+    const bool one_table = p.one_table != 0;
+    const uint32_t vl_norm = one_table ? 0u : (uint32_t)n * LUTB, vl_last = one_table ? 0u : (uint32_t)nc * LUTB;
+    const int64_t lut_tile_bytes = one_table ? 0 : kTile * LUTB;
     const int lr = COARSE ? p.lr : 0, GS = FINE ? 2 * G : G >> lr;      // scales / offsets per row
     const uint32_t vs_norm = (uint32_t)n * (uint32_t)GS * 2u, vs_last = (uint32_t)nc * (uint32_t)GS * 2u;
     const char* const codes_b = reinterpret_cast<const char*>(p.codes);
@@ -259,7 +262,7 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
         }
     };
     auto load_lut = [&](LutSrc& l, int t) {          // straight from memory
-        read_lut_row(l, lut_b + (int64_t)t * (kTile * LUTB) + (t == last_tile ? vl_last : vl_norm));
+        read_lut_row(l, lut_b + (int64_t)t * lut_tile_bytes + (t == last_tile ? vl_last : vl_norm));
     };
     // table of a tile into buffer `par`
     auto build_table = [&](const LutSrc& l, int par) {
@@ -348,7 +351,7 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
                 axo[c].y = *reinterpret_cast<const uint16_t*>(offset_b + tile_off + v + i1);
             }
         }
-        const char* lrow = lut_b + (int64_t)t * (kTile * LUTB) + (t == last_tile ? vl_last : vl_norm);
+        const char* lrow = lut_b + (int64_t)t * lut_tile_bytes + (t == last_tile ? vl_last : vl_norm);
         if constexpr (NOLUT) { (void)lrow; }
         // (every lane loads, also those whose copy is not written to the slot: a load under a per-lane
         // condition is waited for on the spot, together with all the code loads in flight)
@@ -696,7 +699,8 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
         constexpr bool REFILL = decltype(refill)::value;    // false for the block's last tiles
         const int i = t - t0, par = i & 1;
         const int tn = min(t + kDepth, t1 - 1);
-        const uint32_t low = low0 + par * kLowPar;
+        // (one table for the whole matrix: built once, before the first tile, in buffer 0)
+        const uint32_t low = low0 + (one_table ? 0 : par) * kLowPar;
         uint4 bq[2][4];
         auto lookups = [&](int gi, uint4 (&b)[4]) {
             const Quarter c = cw[B][gi];
@@ -721,7 +725,7 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
             if (i + 2 >= kAuxDist && i + 2 < ntiles && w == ((i + 2) & 7)) aux_write((i + 2) & (kAuxDist - 1));
             if (i + kAuxDist < ntiles && w == ((i + kAuxDist) & 7)) aux_load(t + kAuxDist);
             aux_read_so(sp, op, i & (kAuxDist - 1));
-            if (i + 1 < ntiles) {
+            if (i + 1 < ntiles && !one_table) {
                 LutSrc l;
                 aux_read_lut(l, (i + 1) & (kAuxDist - 1));
                 build_table(l, par ^ 1);
@@ -730,7 +734,7 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
             pack_so(sp, op, sraw[B], oraw[B]);
             // the table of the next tile goes into the other buffer (everybody finished with it at the
             // barrier that ended the previous tile); its source registers are then refilled
-            if (i + 1 < ntiles) build_table(lut_ring[B1], par ^ 1);
+            if (i + 1 < ntiles && !one_table) build_table(lut_ring[B1], par ^ 1);
             if constexpr (REFILL) load_lut(lut_ring[B1], min(t + 1 + kDepth, t1 - 1));
         }
         f32x4 acc = mfma(xo, NOLUT ? offset_operand_nolut(sp, op) : offset_operand(op), zero);
@@ -921,7 +925,7 @@ static hipError_t launch_stream_b(const Params& p, const StreamPlan& sp, int gri
 
 hipError_t launch_decode_stream(const uint16_t* x, const uint32_t* codes, const uint16_t* lut,
                                 const uint16_t* scale, const uint16_t* offset, int64_t M, int64_t N,
-                                int64_t K, int bits, int lr, bool repacked, bool f16, const StreamPlan& sp_in, uint16_t* y,
+                                int64_t K, int bits, int lr, bool repacked, bool f16, bool one_table, const StreamPlan& sp_in, uint16_t* y,
                                 void* workspace, hipStream_t stream) {
     const StreamPlan& sp = sp_in;
     Params p{};
@@ -932,6 +936,7 @@ hipError_t launch_decode_stream(const uint16_t* x, const uint32_t* codes, const 
     p.N = N; p.K = K; p.M = (int)M; p.G = (int)(K / kGroup); p.lr = lr;
     p.slabs = sp.slabs; p.slab_groups = sp.slab_groups; p.blocks_per_slab = sp.blocks_per_slab;
     p.tiles = (int)sp.tiles;
+    p.one_table = one_table ? 1 : 0;
     const int grid = sp.slabs * sp.blocks_per_slab;
     if (f16) {
         // fp16: the table-based kernels on the plain layout with groups of 128

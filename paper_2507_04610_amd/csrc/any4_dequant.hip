@@ -16,12 +16,12 @@ __global__ __launch_bounds__(256) void dequant_kernel(const uint32_t* __restrict
                                                       const uint16_t* __restrict__ lut,
                                                       const uint16_t* __restrict__ scale,
                                                       const uint16_t* __restrict__ offset,
-                                                      int64_t K, int lr, float* __restrict__ w) {
+                                                      int64_t K, int lr, int one_table, float* __restrict__ w) {
     constexpr int L = 1 << BITS;
     constexpr uint32_t mask = L - 1;
     __shared__ float table[L];
     const int64_t n = blockIdx.x;
-    if (threadIdx.x < L) table[threadIdx.x] = lut ? h16_to_f32<F16>(lut[n * L + threadIdx.x]) : (float)((int)threadIdx.x - L / 2);   // no table: the integer grid
+    if (threadIdx.x < L) table[threadIdx.x] = lut ? h16_to_f32<F16>(lut[(one_table ? 0 : n * L) + threadIdx.x]) : (float)((int)threadIdx.x - L / 2);   // no table: the integer grid
     __syncthreads();
 
     const uint32_t* row = codes + n * row_words(K, BITS);
@@ -49,13 +49,13 @@ __global__ __launch_bounds__(256) void dequant_kernel(const uint32_t* __restrict
 
 hipError_t launch_dequant(const uint32_t* codes, const uint16_t* lut, const uint16_t* scale,
                           const uint16_t* offset, int64_t N, int64_t K, int bits, int lr, bool f16,
-                          float* w, hipStream_t stream) {
+                          bool one_table, float* w, hipStream_t stream) {
     if (N > 0x7FFFFFFF || K > (int64_t)1 << 28) return hipErrorInvalidValue;
     const dim3 grid((unsigned)N), block(256);
 #define ANY4_DEQUANT(B)                                                                                   \
     do {                                                                                                  \
-        if (f16) hipLaunchKernelGGL((dequant_kernel<B, true>), grid, block, 0, stream, codes, lut, scale, offset, K, lr, w);   \
-        else hipLaunchKernelGGL((dequant_kernel<B, false>), grid, block, 0, stream, codes, lut, scale, offset, K, lr, w);      \
+        if (f16) hipLaunchKernelGGL((dequant_kernel<B, true>), grid, block, 0, stream, codes, lut, scale, offset, K, lr, one_table ? 1 : 0, w);   \
+        else hipLaunchKernelGGL((dequant_kernel<B, false>), grid, block, 0, stream, codes, lut, scale, offset, K, lr, one_table ? 1 : 0, w);      \
     } while (0)
     switch (bits) {
         case 4: ANY4_DEQUANT(4); break;

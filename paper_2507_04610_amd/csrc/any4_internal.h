@@ -43,10 +43,10 @@ struct PackPlan {
     int64_t tiles;        // 16-row tiles
     int nblocks;          // grid size
 };
-PackPlan plan_pack(int64_t M, int64_t N, int64_t K, int bits, int cus);
+PackPlan plan_pack(int64_t M, int64_t N, int64_t K, int bits, bool one_table, int cus);
 hipError_t launch_decode_pack(const uint16_t* x, const uint32_t* codes, const uint16_t* lut,
                               const uint16_t* scale, const uint16_t* offset, int64_t M, int64_t N,
-                              int64_t K, int bits, bool repacked, const PackPlan& pl, uint16_t* y,
+                              int64_t K, int bits, bool repacked, bool one_table, const PackPlan& pl, uint16_t* y,
                               hipStream_t stream);
 
 // How any4_gemm runs a given problem; a pure function of (M, N, K, bits) so that
@@ -66,25 +66,25 @@ GemmPlan plan_gemm(int64_t M, int64_t N, int64_t K, int bits);
 int gemm_dispatch(const uint16_t* x, const uint32_t* codes, bool repacked, const uint16_t* lut,
                   const uint16_t* scale, const uint16_t* offset, int64_t M, int64_t N, int64_t K,
                   int bits, int group, uint16_t* y, void* workspace, size_t workspace_bytes, void* stream,
-                  bool f16);
+                  bool f16, bool one_table);
 
 hipError_t launch_pack(const uint8_t* codes_u8, int64_t N, int64_t K, int bits,
                        uint32_t* codes, hipStream_t stream);
 hipError_t launch_dequant(const uint32_t* codes, const uint16_t* lut, const uint16_t* scale,
                           const uint16_t* offset, int64_t N, int64_t K, int bits, int lr, bool f16,
-                          float* w, hipStream_t stream);
+                          bool one_table, float* w, hipStream_t stream);
 hipError_t launch_decode(const uint16_t* x, const uint32_t* codes, const uint16_t* lut,
                          const uint16_t* scale, const uint16_t* offset,
-                         int64_t M, int64_t N, int64_t K, int bits, const GemmPlan& plan,
+                         int64_t M, int64_t N, int64_t K, int bits, const GemmPlan& plan, bool one_table,
                          uint16_t* y, float* partial, hipStream_t stream);
 hipError_t launch_decode_stream(const uint16_t* x, const uint32_t* codes, const uint16_t* lut,
                                 const uint16_t* scale, const uint16_t* offset, int64_t M, int64_t N,
-                                int64_t K, int bits, int lr, bool repacked, bool f16, const StreamPlan& sp, uint16_t* y,
+                                int64_t K, int bits, int lr, bool repacked, bool f16, bool one_table, const StreamPlan& sp, uint16_t* y,
                                 void* workspace, hipStream_t stream);
 hipError_t launch_reduce_slices(const float* partial, int ksplit, int64_t MN, uint16_t* y, hipStream_t stream);
 hipError_t launch_prefill(const uint16_t* x, const uint32_t* codes, const uint16_t* lut,
                           const uint16_t* scale, const uint16_t* offset,
-                          int64_t M, int64_t N, int64_t K, int bits, int lr, bool repacked, bool f16, int cus,
+                          int64_t M, int64_t N, int64_t K, int bits, int lr, bool repacked, bool f16, bool one_table, int cus,
                           uint16_t* y, void* workspace, hipStream_t stream);
 // Tile-major re-layout of the packed codes (any4_repack).
 hipError_t launch_repack(const uint32_t* codes, int64_t N, int64_t K, int bits, uint32_t* out, hipStream_t stream);

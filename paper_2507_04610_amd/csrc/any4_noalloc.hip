@@ -72,5 +72,5 @@ extern "C" int any4_gemm_noalloc(const uint16_t* x, const uint32_t* codes, const
                            static_cast<hipStream_t>(stream), base, nclear);
         if (hipGetLastError() != hipSuccess) return ANY4_ERR_HIP;
     }
-    return gemm_dispatch(x, codes, false, lut, scale, offset, M, N, K, bits, ANY4_GROUP, y, ws, kScratchBytes, stream, false);
+    return gemm_dispatch(x, codes, false, lut, scale, offset, M, N, K, bits, ANY4_GROUP, y, ws, kScratchBytes, stream, false, false);
 }

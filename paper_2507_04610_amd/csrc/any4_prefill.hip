@@ -95,9 +95,10 @@ __global__ __launch_bounds__(PTHREADS, 1) void prefill_kernel(
     const uint16_t* __restrict__ x, const uint32_t* __restrict__ codes,
     const uint16_t* __restrict__ lut, const uint16_t* __restrict__ scale,
     const uint16_t* __restrict__ offset, const uint16_t* __restrict__ xsums, int KP,
-    int64_t M, int64_t N, int64_t K, int lr, int repacked, int gm, int tail_first, int tail_s,
+    int64_t M, int64_t N, int64_t K, int lr, int flags, int gm, int tail_first, int tail_s,
     unsigned long long* __restrict__ counters, float* __restrict__ partial, uint16_t* __restrict__ y) {
     constexpr int L = 1 << BITS;
+    const bool repacked = flags & 1, one_table = flags & 2;     // re-laid-out codes / one table for all rows
     static_assert(!(F16 && FINE), "fp16 comes with groups of 128 and more");
     using op16x8 = std::conditional_t<F16, f16x8, bf16x8>;
     auto mma = [](const op16x8& a, const op16x8& b, const f32x16& c) -> f32x16 {
@@ -302,7 +303,7 @@ __global__ __launch_bounds__(PTHREADS, 1) void prefill_kernel(
         for (int i = tid; i < PBN * PIECES; i += PTHREADS) {
             const int row = i / PIECES, pc = i % PIECES;
             uint2 v;
-            if (lut) v = *reinterpret_cast<const uint2*>(lut + min(n0 + row, N - 1) * L + pc * 4);
+            if (lut) v = *reinterpret_cast<const uint2*>(lut + (one_table ? 0 : min(n0 + row, N - 1) * L) + pc * 4);
             else {                                             // no table: the integer grid, entries pc * 4 .. + 3
                 const int c0 = pc * 4 - L / 2;
                 v.x = f32_to_h16<F16>((float)c0) | (f32_to_h16<F16>((float)(c0 + 1)) << 16);
@@ -491,7 +492,7 @@ size_t prefill_workspace_bytes(int64_t M, int64_t N, int64_t K, int cus) {
 
 hipError_t launch_prefill(const uint16_t* x, const uint32_t* codes, const uint16_t* lut,
                           const uint16_t* scale, const uint16_t* offset,
-                          int64_t M, int64_t N, int64_t K, int bits, int lr, bool repacked, bool f16, int cus,
+                          int64_t M, int64_t N, int64_t K, int bits, int lr, bool repacked, bool f16, bool one_table, int cus,
                           uint16_t* y, void* workspace, hipStream_t stream) {
     const PrefillPlan pp = plan_prefill(M, N, K, cus);
     const bool fine = lr < 0;
@@ -516,7 +517,7 @@ hipError_t launch_prefill(const uint16_t* x, const uint32_t* codes, const uint16
         e = hipGetLastError();                                                                                    \
         if (e != hipSuccess) return e;                                                                            \
         hipLaunchKernelGGL((prefill_kernel<B, F, H>), grid, block, prefill_lds_bytes(B), stream, x, codes, lut, scale, \
-                           offset, xsums, KP, M, N, K, F ? 0 : lr, repacked ? 1 : 0, gm, tail_first, tail_s, counters, partial, y); \
+                           offset, xsums, KP, M, N, K, F ? 0 : lr, (repacked ? 1 : 0) | (one_table ? 2 : 0), gm, tail_first, tail_s, counters, partial, y); \
     } while (0)
 #define ANY4_PREFILL(B)                                                                                           \
     do {                                                                                                          \

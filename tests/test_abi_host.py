@@ -59,6 +59,8 @@ def test_bad_arguments_are_rejected_before_any_launch(lib):
     assert lib.any4_gemm(A, A, A, A, A, 1, 4, 128, 4, None, None, 0, None) == -1
     assert lib.any4_repack(None, 4, 128, 4, A, None) == -1
     assert lib.any4_gemm_repacked(A, A, None, A, A, 1, 4, 128, 4, A, None, 0, None) == -1     # needs a table
+    assert lib.any4_gemm_single_table(A, A, None, A, A, 1, 4, 128, 4, A, None, 0, None) == -1 # needs its one table
+    assert lib.any4_dequant_single_table(A, None, A, A, 4, 128, 4, A, None) == -1
     # shapes
     assert lib.any4_repack(A, 4, 100, 4, A, None) == -2
     assert lib.any4_repack(A, 4, 128, 5, A, None) == -3
