@@ -90,7 +90,13 @@ __global__ __launch_bounds__(256) void group_sums_kernel(const uint16_t* __restr
 // FINE: groups of 64 weights - every K step is a group of its own (scale index 2g, 2g + 1 for the two
 // steps of chunk g; the offset phase runs over 64-weight groups).  Otherwise groups of 128 << lr.
 // F16: activations, table, scales, offsets and output are fp16 instead of bf16.
-template <int BITS, bool FINE, bool F16>
+// NOLUT: 4-bit codes on the uniform grid (value = code - 8, the int4 format the paper compares with in
+// section 4.2, last paragraph) without any table: a code c becomes the bf16 number 128 + c by OR-ing it
+// into the mantissa of 128.0 (0x4300 | c) - two shifts and two and-or per pair of weights instead of
+// two address computations, two LDS lookups and a pack - and the surplus 136 * scale * X (X = the
+// group sum of the activations) is taken off in the offset phase by two more passes over the same
+// group sums whose right operands are the exact bf16 numbers -128 * scale and -8 * scale.
+template <int BITS, bool FINE, bool F16, bool NOLUT = false>
 __global__ __launch_bounds__(PTHREADS, 1) void prefill_kernel(
     const uint16_t* __restrict__ x, const uint32_t* __restrict__ codes,
     const uint16_t* __restrict__ lut, const uint16_t* __restrict__ scale,
@@ -100,6 +106,7 @@ __global__ __launch_bounds__(PTHREADS, 1) void prefill_kernel(
     constexpr int L = 1 << BITS;
     const bool repacked = flags & 1, one_table = flags & 2;     // re-laid-out codes / one table for all rows
     static_assert(!(F16 && FINE), "fp16 comes with groups of 128 and more");
+    static_assert(!NOLUT || (BITS == 4 && !F16 && !FINE), "the table-free path: 4-bit codes, bf16, groups of 128");
     using op16x8 = std::conditional_t<F16, f16x8, bf16x8>;
     auto mma = [](const op16x8& a, const op16x8& b, const f32x16& c) -> f32x16 {
         if constexpr (F16) return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
@@ -190,6 +197,11 @@ __global__ __launch_bounds__(PTHREADS, 1) void prefill_kernel(
         else v = __builtin_amdgcn_alignbit(hi, lo, bit) << 7;
         return (v & mask) | tbase;
     };
+    // NOLUT: codes 2p, 2p + 1 of a word of eight as the bf16 pair (128 + c, 128 + c')
+    auto grid_pair = [&](uint32_t w, int pi) -> uint32_t {
+        const uint32_t t = w >> (8 * pi);
+        return (t & 0xFu) | ((t << 12) & 0xF0000u) | 0x43004300u;
+    };
     auto code_words = [&](const uint32_t (&q)[2], uint32_t& lo, uint32_t& hi) {
         lo = q[0]; hi = q[1];
         if constexpr (BITS == 3) {
@@ -216,12 +228,16 @@ __global__ __launch_bounds__(PTHREADS, 1) void prefill_kernel(
             }
         };
         auto w_issue = [&](int c, int h) {                      // four of the eight lookups of chunk c
+            if constexpr (NOLUT) return;
 #pragma unroll
             for (int t = 0; t < 4; ++t) lk[c][h * 4 + t] = *reinterpret_cast<lds_u32>(entry_addr(lo, hi, c * 8 + h * 4 + t));
         };
         auto w_finish = [&](int c, int h) {                     // pack half of chunk c; then the 16-byte write
 #pragma unroll
-            for (int t = 0; t < 2; ++t) wpk[h * 2 + t] = lk[c][h * 4 + 2 * t] | (lk[c][h * 4 + 2 * t + 1] << 16);
+            for (int t = 0; t < 2; ++t) {
+                if constexpr (NOLUT) wpk[h * 2 + t] = grid_pair(c ? hi : lo, h * 2 + t);
+                else wpk[h * 2 + t] = lk[c][h * 4 + 2 * t] | (lk[c][h * 4 + 2 * t + 1] << 16);
+            }
             if (h == 1)
                 *reinterpret_cast<lds_u4>(wwr + (BUF ^ 1) * kWBuf + c * 16) = u32x4{wpk[0], wpk[1], wpk[2], wpk[3]};
         };
@@ -298,7 +314,7 @@ __global__ __launch_bounds__(PTHREADS, 1) void prefill_kernel(
     fetch_q(q1, S0 + 1);
     // per-row tables of this block's weight rows (rows past N are clamped: they are never stored):
     // one thread fetches 8 bytes (4 entries) of a row and writes each entry's 4 adjacent copies at once
-    {
+    if constexpr (!NOLUT) {
         constexpr int PIECES = L / 4;                            // 8-byte pieces per row
         for (int i = tid; i < PBN * PIECES; i += PTHREADS) {
             const int row = i / PIECES, pc = i % PIECES;
@@ -326,11 +342,16 @@ __global__ __launch_bounds__(PTHREADS, 1) void prefill_kernel(
         code_words(q0, lo, hi);
 #pragma unroll
         for (int c = 0; c < 2; ++c) {
-            uint32_t v[8];
+            if constexpr (NOLUT) {
+                const uint32_t wd = c ? hi : lo;
+                *reinterpret_cast<lds_u4>(wwr + c * 16) = u32x4{grid_pair(wd, 0), grid_pair(wd, 1), grid_pair(wd, 2), grid_pair(wd, 3)};
+            } else {
+                uint32_t v[8];
 #pragma unroll
-            for (int t = 0; t < 8; ++t) v[t] = *reinterpret_cast<lds_u32>(entry_addr(lo, hi, c * 8 + t));
-            *reinterpret_cast<lds_u4>(wwr + c * 16) =
-                u32x4{v[0] | (v[1] << 16), v[2] | (v[3] << 16), v[4] | (v[5] << 16), v[6] | (v[7] << 16)};
+                for (int t = 0; t < 8; ++t) v[t] = *reinterpret_cast<lds_u32>(entry_addr(lo, hi, c * 8 + t));
+                *reinterpret_cast<lds_u4>(wwr + c * 16) =
+                    u32x4{v[0] | (v[1] << 16), v[2] | (v[3] << 16), v[4] | (v[5] << 16), v[6] | (v[7] << 16)};
+            }
         }
         fetch_q(q0, min(S0 + 2, T - 1));
         fetch_x(S0 + 1);
@@ -370,6 +391,11 @@ __global__ __launch_bounds__(PTHREADS, 1) void prefill_kernel(
     // ---- offset term: a few more K steps over the group dimension (activation group sums split into
     //      bf16 hi + lo in columns 2g, 2g+1; both columns meet offset[n][g]); unscaled
     const int og_lo = FINE ? 2 * g_lo : g_lo, og_hi = FINE ? 2 * g_hi : g_hi;      // this block's groups, in the units of xsums
+    // NOLUT: three passes over the group sums - right operand offset, then -128 * scale and -8 * scale (the
+    // bf16 scale with 7 / 3 added to its exponent and the sign flipped: exact)
+    constexpr int kKinds = NOLUT ? 3 : 1;
+#pragma unroll
+    for (int kind = 0; kind < kKinds; ++kind)
     for (int k0 = 2 * og_lo / PBK * PBK; k0 < 2 * og_hi; k0 += PBK) {
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
@@ -380,7 +406,10 @@ __global__ __launch_bounds__(PTHREADS, 1) void prefill_kernel(
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const int gg = (k0 + wq * 16 + 2 * j) >> 1;
-            const uint32_t b = gg >= og_lo && gg < og_hi ? offset[wn_glob * GS + (FINE ? gg : gg >> lr)] : 0u;
+            const bool in = gg >= og_lo && gg < og_hi;
+            uint32_t b = in ? (kind == 0 ? offset : scale)[wn_glob * GS + (FINE ? gg : gg >> lr)] : 0u;
+            if (kind == 1) b = in ? (b + 0x0380u) ^ 0x8000u : 0u;
+            if (kind == 2) b = in ? (b + 0x0180u) ^ 0x8000u : 0u;
             pk[j] = b | (b << 16);
         }
 #pragma unroll
@@ -508,22 +537,23 @@ hipError_t launch_prefill(const uint16_t* x, const uint32_t* codes, const uint16
     const int gm = (int)pp.gm, tail_first = (int)(pp.tiles - pp.tail_tiles), tail_s = pp.tail_s;
     // the LDS limit first: whatever can be refused is refused before anything is enqueued
     hipError_t e = hipSuccess;
-#define ANY4_PREFILL_F(B, F, H)                                                                                   \
+#define ANY4_PREFILL_F(B, F, H, NL)                                                                                 \
     do {                                                                                                          \
-        e = ensure_lds<prefill_kernel<B, F, H>>((int)prefill_lds_bytes(B));                                       \
+        e = ensure_lds<prefill_kernel<B, F, H, NL>>((int)prefill_lds_bytes(B));                                       \
         if (e != hipSuccess) return e;                                                                            \
         if (f16) hipLaunchKernelGGL(group_sums_kernel<true>, dim3((unsigned)sblocks), dim3(256), 0, stream, x, M, K, KP, 0, xsums); \
         else hipLaunchKernelGGL(group_sums_kernel<false>, dim3((unsigned)sblocks), dim3(256), 0, stream, x, M, K, KP, fine ? 1 : 0, xsums); \
         e = hipGetLastError();                                                                                    \
         if (e != hipSuccess) return e;                                                                            \
-        hipLaunchKernelGGL((prefill_kernel<B, F, H>), grid, block, prefill_lds_bytes(B), stream, x, codes, lut, scale, \
+        hipLaunchKernelGGL((prefill_kernel<B, F, H, NL>), grid, block, prefill_lds_bytes(B), stream, x, codes, lut, scale, \
                            offset, xsums, KP, M, N, K, F ? 0 : lr, (repacked ? 1 : 0) | (one_table ? 2 : 0), gm, tail_first, tail_s, counters, partial, y); \
     } while (0)
 #define ANY4_PREFILL(B)                                                                                           \
     do {                                                                                                          \
-        if (f16) ANY4_PREFILL_F(B, false, true);                                                                  \
-        else if (fine) ANY4_PREFILL_F(B, true, false);                                                            \
-        else ANY4_PREFILL_F(B, false, false);                                                                     \
+        if (B == 4 && !lut && !f16 && !fine && lr == 0) ANY4_PREFILL_F(4, false, false, true);                    \
+        else if (f16) ANY4_PREFILL_F(B, false, true, false);                                                             \
+        else if (fine) ANY4_PREFILL_F(B, true, false, false);                                                            \
+        else ANY4_PREFILL_F(B, false, false, false);                                                                     \
     } while (0)
     switch (bits) {
         case 4: ANY4_PREFILL(4); break;

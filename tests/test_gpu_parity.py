@@ -182,12 +182,13 @@ def test_gemm_other_4bit_formats_through_the_table(any4, oracle, M):
 
 
 @pytest.mark.parametrize("M,N,K", [(1, 333, 4224), (1, 64, 128), (3, 17, 384), (8, 700, 640), (16, 100, 4480),
-                                   (2, 48, 14336), (16, 33, 8192), (40, 200, 1024), (300, 130, 640)])
+                                   (2, 48, 14336), (16, 33, 8192), (40, 200, 1024), (300, 130, 640),
+                                   (129, 260, 4224), (600, 140, 8192), (257, 1100, 384)])
 def test_gemm_int4_grid_without_table(any4, oracle, M, N, K):
     """lut = NULL with 4-bit codes: the uniform integer grid (value = code - 8).  The oracle runs the
-    same problem with that grid written out as every row's table; the device runs it table-free
-    (M <= 16) or with the grid synthesised inside the kernel (larger M), and the dequantised weights
-    agree bit for bit."""
+    same problem with that grid written out as every row's table; the device runs it table-free at
+    every M (codes OR-ed into the mantissa of 128.0, the surplus taken off through the group sums of x),
+    and the dequantised weights agree bit for bit."""
     cs = inputs.make_case(M, N, K, 4, seed=inputs.case_seed(11, 4, M % 10))
     cs.lut[:] = inputs.f32_to_bf16_bits(np.arange(-8, 8, dtype=np.float32))
     packed = oracle.pack(cs.codes_u8, 4)
