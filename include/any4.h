@@ -229,6 +229,25 @@ int any4_quantize(const float* w, const float* act, const float* u, int64_t N, i
                   int bits, int symmetric, int iters, uint8_t* codes_u8, uint16_t* lut,
                   uint16_t* scale, uint16_t* offset, int32_t* msteps, void* stream);
 
+/*
+ * any4_quantize_with_gap - any4_quantize with its one tuning knob exposed.  Rows of K <= 16384 are
+ * sorted once, after which a Lloyd pass (section 3.2, E-step and M-step) costs O(2^bits log K): the
+ * clusters are runs of the sorted row, found by binary search with the E-step's own comparison, and
+ * their sums are differences of running sums.  That search presumes that unequal centres are further
+ * apart than the rounding of a distance; a row in which two unequal centres come closer than
+ * centre_gap * max|w_S| is done again from its starting centres by the plain method (every weight
+ * against every centre in every pass), which is also the method of longer rows.
+ *   centre_gap  >= 0: as described (any4_quantize passes 2^-40); a huge value sends every row with two
+ *               unequal centres through the hand-over; < 0: the plain method for all rows.
+ * Both methods take every decision in fp64 on the same fp32 inputs and differ only in the
+ * association of the fp64 sums.  All other arguments, errors and limits as any4_quantize; NaN for
+ * centre_gap returns ANY4_ERR_SHAPE.
+ */
+int any4_quantize_with_gap(const float* w, const float* act, const float* u, int64_t N, int64_t K,
+                           int bits, int symmetric, int iters, double centre_gap, uint8_t* codes_u8,
+                           uint16_t* lut, uint16_t* scale, uint16_t* offset, int32_t* msteps,
+                           void* stream);
+
 /* Largest K any4_quantize accepts. */
 int64_t any4_quantize_max_k(void);
 

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_PKG, "libany4.so")
 GROUP = 128
 
 EXPORTS = ("any4_pack", "any4_dequant", "any4_gemm", "any4_gemm_workspace_bytes", "any4_repack", "any4_repack_bytes", "any4_gemm_repacked", "any4_dequant_grouped", "any4_gemm_grouped", "any4_dequant_f16", "any4_gemm_f16",
-           "any4_quantize", "any4_quantize_max_k", "any4_gemm_noalloc", "any4_dequant_single_table", "any4_gemm_single_table", "any4_strerror", "any4_version")
+           "any4_quantize", "any4_quantize_with_gap", "any4_quantize_max_k", "any4_gemm_noalloc", "any4_dequant_single_table", "any4_gemm_single_table", "any4_strerror", "any4_version")
 
 
 class Any4Error(RuntimeError):
@@ -68,6 +68,8 @@ def load_library() -> ctypes.CDLL:
     lib.any4_repack_bytes.argtypes = [i64, i64, ci]
     lib.any4_quantize.restype = ci
     lib.any4_quantize.argtypes = [vp, vp, vp, i64, i64, ci, ci, ci, vp, vp, vp, vp, vp, vp]
+    lib.any4_quantize_with_gap.restype = ci
+    lib.any4_quantize_with_gap.argtypes = [vp, vp, vp, i64, i64, ci, ci, ci, ctypes.c_double, vp, vp, vp, vp, vp, vp]
     lib.any4_quantize_max_k.restype = i64
     lib.any4_quantize_max_k.argtypes = []
     lib.any4_strerror.restype = ctypes.c_char_p
@@ -290,10 +292,11 @@ def any4_quantize_max_k() -> int:
 
 
 def any4_quantize(w: torch.Tensor, act: torch.Tensor | None, u: torch.Tensor, bits: int = 4,
-                  symmetric: bool = False, iters: int = 20):
+                  symmetric: bool = False, iters: int = 20, centre_gap: float | None = None):
     """fp32 [N,K] weights, fp32 [K] mean |activation| per channel (or None), fp32 [N, 2^bits]
     uniform draws -> dict with codes_u8 uint8 [N,K], lut bf16 [N,2^bits], scale / offset bf16
-    [N,K/128] and msteps int32 [N].  Everything stays in device memory."""
+    [N,K/128] and msteps int32 [N].  Everything stays in device memory.  centre_gap: None calls
+    any4_quantize, a number calls any4_quantize_with_gap."""
     lib = load_library()
     N, K = w.shape
     L = 1 << bits
@@ -308,6 +311,11 @@ def any4_quantize(w: torch.Tensor, act: torch.Tensor | None, u: torch.Tensor, bi
     scale = torch.empty((N, max(K // GROUP, 0)), dtype=torch.bfloat16, device=dev)
     offset = torch.empty((N, max(K // GROUP, 0)), dtype=torch.bfloat16, device=dev)
     msteps = torch.empty((N,), dtype=torch.int32, device=dev)
-    _check(lib.any4_quantize(pw, pa, pu, N, K, bits, int(symmetric), iters, codes.data_ptr(), lut.data_ptr(),
-                             scale.data_ptr(), offset.data_ptr(), msteps.data_ptr(), _stream()), "any4_quantize")
+    if centre_gap is None:
+        _check(lib.any4_quantize(pw, pa, pu, N, K, bits, int(symmetric), iters, codes.data_ptr(), lut.data_ptr(),
+                                 scale.data_ptr(), offset.data_ptr(), msteps.data_ptr(), _stream()), "any4_quantize")
+    else:
+        _check(lib.any4_quantize_with_gap(pw, pa, pu, N, K, bits, int(symmetric), iters, float(centre_gap),
+                                          codes.data_ptr(), lut.data_ptr(), scale.data_ptr(), offset.data_ptr(),
+                                          msteps.data_ptr(), _stream()), "any4_quantize_with_gap")
     return {"codes_u8": codes, "lut": lut, "scale": scale, "offset": offset, "msteps": msteps}

@@ -223,18 +223,25 @@ int any4_dequant(const uint32_t* codes, const uint16_t* lut, const uint16_t* sca
 
 int64_t any4_quantize_max_k(void) { return (int64_t)quantize_max_k(); }
 
-int any4_quantize(const float* w, const float* act, const float* u, int64_t N, int64_t K, int bits,
-                  int symmetric, int iters, uint8_t* codes_u8, uint16_t* lut, uint16_t* scale,
-                  uint16_t* offset, int32_t* msteps, void* stream) {
+int any4_quantize_with_gap(const float* w, const float* act, const float* u, int64_t N, int64_t K, int bits,
+                           int symmetric, int iters, double centre_gap, uint8_t* codes_u8, uint16_t* lut,
+                           uint16_t* scale, uint16_t* offset, int32_t* msteps, void* stream) {
     if (!w || !u || !codes_u8 || !lut || !scale || !offset) return ANY4_ERR_NULL;
     if (int rc = shape_check(N, K, bits)) return rc;
-    if (K > (int64_t)quantize_max_k() || iters < 0) return ANY4_ERR_SHAPE;
+    if (K > (int64_t)quantize_max_k() || iters < 0 || centre_gap != centre_gap) return ANY4_ERR_SHAPE;
     if (!aligned16(w) || !aligned16(u) || !aligned16(codes_u8) || !aligned16(lut) || !aligned16(scale) ||
         !aligned16(offset) || (act && !aligned16(act)) || (msteps && !aligned16(msteps)))
         return ANY4_ERR_ALIGN;
-    return launch_quantize(w, act, u, N, K, bits, symmetric ? 1 : 0, iters, codes_u8, lut, scale, offset, msteps,
-                           static_cast<hipStream_t>(stream)) == hipSuccess
+    return launch_quantize(w, act, u, N, K, bits, symmetric ? 1 : 0, iters, centre_gap, codes_u8, lut, scale, offset,
+                           msteps, static_cast<hipStream_t>(stream)) == hipSuccess
                ? ANY4_OK : ANY4_ERR_HIP;
+}
+
+int any4_quantize(const float* w, const float* act, const float* u, int64_t N, int64_t K, int bits,
+                  int symmetric, int iters, uint8_t* codes_u8, uint16_t* lut, uint16_t* scale,
+                  uint16_t* offset, int32_t* msteps, void* stream) {
+    return any4_quantize_with_gap(w, act, u, N, K, bits, symmetric, iters, kQuantizeCentreGap, codes_u8, lut, scale,
+                                  offset, msteps, stream);
 }
 
 size_t any4_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int bits) {

@@ -101,10 +101,13 @@ struct PrefillPlan {
 PrefillPlan plan_prefill(int64_t M, int64_t N, int64_t K, int cus);
 size_t prefill_workspace_bytes(int64_t M, int64_t N, int64_t K, int cus);
 
-// Quantiser: one block per row, the row lives in LDS, which bounds K.
+// Quantiser: one block per row, the row lives in LDS, which bounds K.  centre_gap < 0: every row by the
+// per-weight method; otherwise rows of K <= 16384 are sorted once and a row falls back to the per-weight
+// method when two unequal centres come closer than centre_gap * max|w_S|.
 size_t quantize_max_k();
+constexpr double kQuantizeCentreGap = 9.094947017729282e-13;      // 2^-40: ~2^12 roundings of a distance
 hipError_t launch_quantize(const float* w, const float* act, const float* u, int64_t N, int64_t K, int bits,
-                           int symmetric, int iters, uint8_t* codes, uint16_t* lut, uint16_t* scale,
+                           int symmetric, int iters, double centre_gap, uint8_t* codes, uint16_t* lut, uint16_t* scale,
                            uint16_t* offset, int32_t* msteps, hipStream_t stream);
 
 }  // namespace any4

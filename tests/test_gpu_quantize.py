@@ -35,18 +35,29 @@ def bits16(t):
     return t.view(torch.int16).cpu().numpy().view(np.uint16)
 
 
-def run_and_compare(any4, qoracle, w, act, u, bits, symmetric, iters, what):
+def run_and_compare(any4, qoracle, w, act, u, bits, symmetric, iters, what, centre_gap=None, by_value=()):
+    """Bit-exact comparison of everything the quantiser returns.  Rows listed in `by_value` are rows with
+    fewer distinct values than centres whose values are not short binary fractions: the weighted mean of
+    equal numbers is that number or a neighbour depending on how the fp64 sum is associated, and with it
+    whether the weights then move on to an equal centre.  Those rows are compared by the table value every
+    weight ends up with (plus scales and offsets), not by code numbering and update count."""
     ref = qoracle.quantize(w, act, u, bits, symmetric=symmetric, iters=iters, threads=8)
     got = any4.any4_quantize(torch.from_numpy(w).cuda(), None if act is None else torch.from_numpy(act).cuda(),
-                             torch.from_numpy(u).cuda(), bits, symmetric=symmetric, iters=iters)
+                             torch.from_numpy(u).cuda(), bits, symmetric=symmetric, iters=iters, centre_gap=centre_gap)
     torch.cuda.synchronize()
+    exact = np.array([i not in by_value for i in range(w.shape[0])])
     assert np.array_equal(bits16(got["scale"]), ref["scale"]), (what, "scale")
     assert np.array_equal(bits16(got["offset"]), ref["offset"]), (what, "offset")
-    assert np.array_equal(got["msteps"].cpu().numpy(), ref["msteps"]), (what, "msteps")
-    assert np.array_equal(bits16(got["lut"]), ref["lut"]), (what, "lut")
+    assert np.array_equal(got["msteps"].cpu().numpy()[exact], ref["msteps"][exact]), (what, "msteps")
+    lut = bits16(got["lut"])
+    assert np.array_equal(lut[exact], ref["lut"][exact]), (what, "lut")
     codes = got["codes_u8"].cpu().numpy()
-    bad = np.argwhere(codes != ref["codes_u8"])
+    bad = np.argwhere(codes[exact] != ref["codes_u8"][exact])
     assert bad.size == 0, (what, "codes", bad[:5].tolist(), len(bad))
+    assert int(codes.max()) < (1 << bits)
+    rec_got = np.take_along_axis(lut, codes.astype(np.int64), axis=1)
+    rec_ref = np.take_along_axis(ref["lut"], ref["codes_u8"].astype(np.int64), axis=1)
+    assert np.array_equal(rec_got, rec_ref), (what, "table value per weight")
     return got, ref
 
 
@@ -55,6 +66,43 @@ def run_and_compare(any4, qoracle, w, act, u, bits, symmetric, iters, what):
 def test_quantize_matches_oracle(any4, qoracle, bits, N, K):
     qc = inputs.make_quant_case(N, K, bits, seed=40 + bits)
     run_and_compare(any4, qoracle, qc.w, qc.act, qc.u, bits, False, 25, (bits, N, K))
+
+
+# the three ways through the kernels: every row by the per-weight method; rows sorted once (what any4_quantize
+# does up to K = 16384); sorted rows that all hand over to the per-weight method in their first pass
+METHODS = {"per_weight": -1.0, "sorted": 2.0 ** -40, "hand_over": 1e300}
+
+
+@pytest.mark.parametrize("method", sorted(METHODS))
+@pytest.mark.parametrize("bits", (4, 3, 2))
+@pytest.mark.parametrize("N,K", [(5, 384), (33, 4096), (6, 8192), (5, 12288), (4, 16384)])
+def test_quantize_methods_match_oracle(any4, qoracle, bits, N, K, method):
+    qc = inputs.make_quant_case(N, K, bits, seed=140 + bits + K % 7)
+    run_and_compare(any4, qoracle, qc.w, qc.act, qc.u, bits, False, 30, (method, bits, N, K), centre_gap=METHODS[method])
+
+
+@pytest.mark.parametrize("method", sorted(METHODS))
+def test_quantize_methods_symmetric_caps_and_degenerate_rows(any4, qoracle, method):
+    gap = METHODS[method]
+    qc = inputs.make_quant_case(7, 1024, 4, seed=17)
+    run_and_compare(any4, qoracle, qc.w, qc.act, qc.u, 4, True, 25, (method, "symmetric"), centre_gap=gap)
+    for iters in (0, 1, 2, 300):
+        run_and_compare(any4, qoracle, qc.w, None, qc.u, 4, False, iters, (method, "iters", iters), centre_gap=gap)
+    w = qc.w.copy()
+    w[0, 128:256] = 0.25
+    w[1, :] = -0.5
+    w[2, :] = np.tile(np.array([-1.0, -0.25, 0.5, 0.875], np.float32), 256)
+    w[3, :] = 0.0
+    w[4, ::2] = -w[4, 1::2]                                 # pairs of equal magnitude: ties between centres
+    act = qc.act.copy()
+    act[::3] = 0.0
+    for bits in (4, 3, 2):
+        u = qc.u[:, :1 << bits].copy()
+        # row 1 (constant) scales to exactly 0 without an offset-free scale; row 2 to four values that are no
+        # short binary fractions
+        run_and_compare(any4, qoracle, w, act, u, bits, False, 20, (method, "degenerate", bits), centre_gap=gap, by_value=(2,))
+        run_and_compare(any4, qoracle, w, act, u, bits, True, 20, (method, "degenerate, symmetric", bits), centre_gap=gap,
+                        by_value=(1, 2))
 
 
 @pytest.mark.parametrize("bits", (4, 3, 2))
@@ -88,7 +136,7 @@ def test_quantize_degenerate_rows(any4, qoracle):
     w[2, :] = np.tile(np.array([-1.0, -0.25, 0.5, 0.875], np.float32), 128)   # 4 distinct values
     act = qc.act.copy()
     act[::3] = 0.0
-    got, ref = run_and_compare(any4, qoracle, w, act, qc.u, 4, False, 20, "degenerate")
+    got, ref = run_and_compare(any4, qoracle, w, act, qc.u, 4, False, 20, "degenerate", by_value=(2,))
     lut = inputs.bf16_bits_to_f32(ref["lut"])
     sc = inputs.bf16_bits_to_f32(ref["scale"]).repeat(128, axis=1)
     of = inputs.bf16_bits_to_f32(ref["offset"]).repeat(128, axis=1)
