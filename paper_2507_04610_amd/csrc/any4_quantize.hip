@@ -421,33 +421,95 @@ __device__ __forceinline__ float key_f32(uint32_t k) {
 }
 constexpr uint32_t kPadKey = 0xFFFFFFFFu;         // sorts after every number; its sample weight is 0
 
-// One round of the bitonic network on the 16 elements a thread holds: the elements differ in bits
-// WB .. WB + NB - 1 of their position (16 / 2^NB independent groups per thread); the round runs the
-// compare-exchange stages of merge size 2^m for the strides 2^top .. 2^WB.  Pairs that sort descending
-// (bit m of the position set) have their keys complemented on the way in and out, so that every
-// compare-exchange is the same ascending one.
-template <int T, int WB, int NB>
-__device__ __forceinline__ void sort_round(uint2* kv, int m, int top) {
-    constexpr int E = 1 << NB;
-    // (the empty asm statement ties the addresses to this call: computed once for all calls, outside the
-    // loop over the merge sizes, the four rounds' addresses would hold ~150 registers)
-    int tid = threadIdx.x;
-    asm volatile("" : "+v"(tid));
+// Compare-exchange of two elements (key, sample weight): the smaller key goes to the first.
+// (The empty asm statement keeps the two sample weights plain values: left alone, the compiler turns
+// "one or the other element of the array" into an element picked by a computed index, which costs a
+// chain of 16 selects per compare-exchange.)
+__device__ __forceinline__ void compare_exchange(uint32_t& k1, uint32_t& s1, uint32_t& k2, uint32_t& s2) {
+    uint32_t a = s1, b = s2;
+    asm("" : "+v"(a), "+v"(b));
+    const bool sw = k1 > k2;
+    const uint32_t ka = min(k1, k2), kb = max(k1, k2);
+    s1 = sw ? b : a;
+    s2 = sw ? a : b;
+    k1 = ka;
+    k2 = kb;
+}
+
+// The first four merge sizes (2 .. 16) of the bitonic network stay inside the 16 neighbouring elements
+// of a thread: one trip through LDS.  Up to size 8 the direction of a pair is a bit of its place among
+// the 16 (known when compiling: descending = the roles swapped); for size 16 it is the thread's parity.
+template <int T>
+__device__ __forceinline__ void sort_first16(uint2* kv) {
+    int base = threadIdx.x * 17;
+    asm volatile("" : "+v"(base));
     uint32_t kk[16], ss[16];
-    int adr[16];
-    uint32_t down = 0;                                             // bit r: element r's pair sorts descending
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-        const int e = r & (E - 1), low = (r >> NB) * T + tid;
-        const int pos = ((low >> WB) << (WB + NB)) | (e << WB) | (low & ((1 << WB) - 1));
-        down |= (((uint32_t)pos >> m) & 1u) << r;
-        adr[r] = pad16(pos);
-        const uint2 v = kv[adr[r]];
+        const uint2 v = kv[base + r];
         kk[r] = v.x;
         ss[r] = v.y;
     }
 #pragma unroll
-    for (int r = 0; r < 16; ++r) kk[r] ^= (uint32_t)((int32_t)(down << (31 - r)) >> 31);
+    for (int m = 1; m <= 4; ++m) {
+        const uint32_t flip = m == 4 ? (uint32_t)(-(int)(threadIdx.x & 1)) : 0u;
+        if (m == 4) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) kk[r] ^= flip;
+        }
+#pragma unroll
+        for (int b = m - 1; b >= 0; --b) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                if ((r & (1 << b)) != 0) continue;
+                const int r2 = r | (1 << b);
+                if (m < 4 && ((r >> m) & 1)) compare_exchange(kk[r2], ss[r2], kk[r], ss[r]);
+                else compare_exchange(kk[r], ss[r], kk[r2], ss[r2]);
+            }
+        }
+        if (m == 4) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) kk[r] ^= flip;
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) kv[base + r] = make_uint2(kk[r], ss[r]);
+    __syncthreads();
+}
+
+// One round of the bitonic network on the 16 elements a thread holds: the elements differ in bits
+// WB .. WB + NB - 1 of their position (16 / 2^NB independent groups per thread); the round runs the
+// compare-exchange stages of merge size 2^m (m > top) for the strides 2^top .. 2^WB.  Pairs that sort
+// descending (bit m of the position set) have their keys complemented on the way in and out, so that every
+// compare-exchange is the same ascending one.  With the spare element after every 16, the 2^NB elements
+// of a group lie a fixed distance apart.
+template <int T, int WB, int NB>
+__device__ __forceinline__ void sort_round(uint2* kv, int m, int top) {
+    constexpr int E = 1 << NB, GROUPS = 16 / E;
+    constexpr int STRIDE = WB >= 4 ? (1 << WB) + (1 << (WB >= 4 ? WB - 4 : 0)) : 1;
+    // (the empty asm statement ties the addresses to this call: computed once for all calls, outside the
+    // loop over the merge sizes, they would hold registers through the whole sort)
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
+    const bool inside = m < WB + NB;                   // the direction bit is one of the bits the 2^NB elements differ in
+    uint32_t kk[16], ss[16], flip[16];
+    int base[GROUPS];
+#pragma unroll
+    for (int g = 0; g < GROUPS; ++g) {
+        const int low = g * T + tid;
+        const int pos0 = ((low >> WB) << (WB + NB)) | (low & ((1 << WB) - 1));
+        base[g] = pos0 + (pos0 >> 4);
+        const uint32_t gflip = inside ? 0u : (uint32_t)(-(int)(((uint32_t)low >> (m - NB)) & 1u));
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            const int r = g * E + e;
+            const uint32_t eflip = inside ? (uint32_t)(-(int)(((uint32_t)e >> (m - WB)) & 1u)) : 0u;   // the same in all lanes
+            flip[r] = gflip | eflip;
+            const uint2 v = kv[base[g] + e * STRIDE];
+            kk[r] = v.x ^ flip[r];
+            ss[r] = v.y;
+        }
+    }
 #pragma unroll
     for (int b = NB - 1; b >= 0; --b) {
         if (WB + b > top) continue;
@@ -455,24 +517,16 @@ __device__ __forceinline__ void sort_round(uint2* kv, int m, int top) {
         for (int r = 0; r < 16; ++r) {
             if ((r & (1 << b)) != 0) continue;
             const int r2 = r | (1 << b);
-            // (the empty asm statement keeps the two sample weights plain values: left alone, the compiler
-            // turns "one or the other element of ss" into an element picked by a computed index, which
-            // costs a chain of 16 selects per compare-exchange)
-            uint32_t s1 = ss[r], s2 = ss[r2];
-            asm("" : "+v"(s1), "+v"(s2));
-            const bool sw = kk[r] > kk[r2];
-            const uint32_t ka = min(kk[r], kk[r2]), kb = max(kk[r], kk[r2]);
-            ss[r] = sw ? s2 : s1;
-            ss[r2] = sw ? s1 : s2;
-            kk[r] = ka;
-            kk[r2] = kb;
+            compare_exchange(kk[r], ss[r], kk[r2], ss[r2]);
         }
     }
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        kk[r] ^= (uint32_t)((int32_t)(down << (31 - r)) >> 31);
-        kv[adr[r]] = make_uint2(kk[r], ss[r]);
-    }
+    for (int g = 0; g < GROUPS; ++g)
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            const int r = g * E + e;
+            kv[base[g] + e * STRIDE] = make_uint2(kk[r] ^ flip[r], ss[r]);
+        }
     __syncthreads();
 }
 
@@ -597,7 +651,8 @@ __global__ __launch_bounds__(T, 4) void quantize_sorted_kernel(
 #pragma unroll
         for (int e = 0; e < 16; ++e) kv[pad16(tid * 16 + e)] = make_uint2(k0[e], s0[e]);
         __syncthreads();
-        for (int m = 1; m <= LOGKP; ++m) {
+        sort_first16<T>(kv);
+        for (int m = 5; m <= LOGKP; ++m) {
             const int top = m - 1;
             if constexpr (LOGKP > 12) {
                 if (top >= 12) sort_round<T, 12, LOGKP - 12>(kv, m, top);
