@@ -29,6 +29,8 @@
 // The sample weights are never stored: s = alpha[group] * act[k] is one fp32 multiply.
 #include "any4_device.h"
 #include "any4_internal.h"
+#include <type_traits>
+#include <utility>
 
 #pragma clang fp contract(off)
 
@@ -56,6 +58,56 @@ __device__ __forceinline__ double shfl_f64(double v, int src) {
     return __hiloint2double(hi, lo);
 }
 
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>), in order
+template <class F, int... I> __device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F> __device__ __forceinline__ void static_for(F&& f) {
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
+// Lane `src` (a constant) of a double, for every lane: two scalar reads, no trip through the LDS pipe.
+template <int SRC>
+__device__ __forceinline__ double lane_f64(double v) {
+    return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), SRC), __builtin_amdgcn_readlane(__double2loint(v), SRC));
+}
+// The double `d` lanes down the same row of 16 lanes (0.0 where the row ends): a DPP move per half.
+template <int D>
+__device__ __forceinline__ double row_shr_f64(double v) {
+    return __hiloint2double(__builtin_amdgcn_update_dpp(0, __double2hiint(v), 0x110 + D, 0xF, 0xF, false),
+                            __builtin_amdgcn_update_dpp(0, __double2loint(v), 0x110 + D, 0xF, 0xF, false));
+}
+// Inclusive sum over the 64 lanes: along the rows of 16 by DPP moves, then the three row totals (scalars)
+// onto the rows after them.  A fixed order of additions, like every sum here.
+__device__ __forceinline__ double wave_inclusive_sum(double v, int lane) {
+    v += row_shr_f64<1>(v);
+    v += row_shr_f64<2>(v);
+    v += row_shr_f64<4>(v);
+    v += row_shr_f64<8>(v);
+    const double t0 = lane_f64<15>(v), t1 = lane_f64<31>(v), t2 = lane_f64<47>(v);
+    const double o2 = t0 + t1, o3 = o2 + t2;
+    const int row = lane >> 4;
+    const double off = row == 0 ? 0.0 : row == 1 ? t0 : row == 2 ? o2 : o3;
+    return v + off;
+}
+// min / max over the 64 lanes (the same value in every lane): within rows of 16 by DPP, then four scalars
+template <bool MAX>
+__device__ __forceinline__ float wave_minmax(float v) {
+    auto pick = [](float a, float b) { return MAX ? fmaxf(a, b) : fminf(a, b); };
+    auto dpp = [](float x, auto ctrl) {
+        return __uint_as_float(__builtin_amdgcn_update_dpp(__float_as_uint(x), __float_as_uint(x), decltype(ctrl)::value, 0xF, 0xF, false));
+    };
+    v = pick(v, dpp(v, std::integral_constant<int, 0xB1>{}));     // lanes 1 0 3 2 of each four
+    v = pick(v, dpp(v, std::integral_constant<int, 0x4E>{}));     // lanes 2 3 0 1
+    v = pick(v, dpp(v, std::integral_constant<int, 0x141>{}));    // the half row mirrored
+    v = pick(v, dpp(v, std::integral_constant<int, 0x140>{}));    // the row mirrored
+    const float a = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(v), 0));
+    const float b = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(v), 16));
+    const float c = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(v), 32));
+    const float d = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(v), 48));
+    return pick(pick(a, b), pick(c, d));
+}
+
 // ---- 1. group-wise scaling (section 2.5.1): scaled row to ws, group scales to alpha (both LDS)
 template <int BITS, int T>
 __device__ __forceinline__ void scale_row(const float* __restrict__ wrow, int64_t n, int G, int symmetric,
@@ -66,13 +118,8 @@ __device__ __forceinline__ void scale_row(const float* __restrict__ wrow, int64_
     const float qrange = symmetric ? (float)((1 << (BITS - 1)) - 1) : (float)(L - 1);
     for (int g = wv; g < G; g += T / kWave) {
         const float2 v = reinterpret_cast<const float2*>(wrow + (int64_t)g * kGroup)[lane];
-        float mn = fminf(v.x, v.y), mx = fmaxf(v.x, v.y), am = fmaxf(fabsf(v.x), fabsf(v.y));
-#pragma unroll
-        for (int m = 1; m < 64; m <<= 1) {
-            mn = fminf(mn, __shfl_xor(mn, m));
-            mx = fmaxf(mx, __shfl_xor(mx, m));
-            am = fmaxf(am, __shfl_xor(am, m));
-        }
+        const float mn = wave_minmax<false>(fminf(v.x, v.y)), mx = wave_minmax<true>(fmaxf(v.x, v.y));
+        const float am = fmaxf(fabsf(mn), fabsf(mx));             // the largest magnitude is at one of the two ends
         const float a32 = symmetric ? am / qrange : (mx - mn) / qrange;
         const float b32 = symmetric ? 0.0f : mn;
         uint32_t ab = f32_to_bf16(a32);
@@ -402,12 +449,13 @@ __global__ __launch_bounds__(QT) void quantize_kernel(
 //                       the elements (order-preserving integer image of w_S, sample weight s as fp32 bits),
 //                       ascending in w_S.  (The per-weight method keeps its codes behind the scaled weights.)
 //   alpha, beta [KP/128] f32 | pre_s, pre_sx [T + 1] f64 (running sums before every 16th sorted element; the total)
-//   scan [2 W] f64 | red [W][2][L] f64 | cen [L] f64 | cen0 [L] f64 | fin [L] u32 | misc [64] i32
+//   scan [2 W] f64 | cen [L] f64 | cen0 [L] f64 | fin [L] u32 | misc [64] i32
+//   (the per-weight method's partial sums red [W][2][L] f64 lie over pre_s: 2 W L <= 2 (T + 1))
 constexpr int kSortedMaxK = 16384;
 constexpr size_t sorted_padw(int T) { return (size_t)T * 17; }
 constexpr size_t sorted_lds_bytes(int T, int bits) {
     const size_t W = (size_t)T / kWave, L = (size_t)1 << bits;
-    return sorted_padw(T) * 8 + 2 * ((size_t)T / 8) * 4 + 2 * ((size_t)T + 1) * 8 + 2 * W * 8 + W * 2 * L * 8 + 2 * L * 8 + L * 4 + 64 * 4;
+    return sorted_padw(T) * 8 + 2 * ((size_t)T / 8) * 4 + 2 * ((size_t)T + 1) * 8 + 2 * W * 8 + 2 * L * 8 + L * 4 + 64 * 4;
 }
 
 __device__ __forceinline__ int pad16(int p) { return p + (p >> 4); }
@@ -549,8 +597,8 @@ __global__ __launch_bounds__(T, 4) void quantize_sorted_kernel(
     double* pre_s = reinterpret_cast<double*>(beta + T / 8);   // [T + 1]
     double* pre_sx = pre_s + T + 1;             // [T + 1]
     double* scan = pre_sx + T + 1;              // [2 W]
-    double* red = scan + 2 * W;                 // [W][2][L]
-    double* cen = red + W * 2 * L;              // [L]
+    double* red = pre_s;                        // [W][2][L], per-weight method only: it has no running sums
+    double* cen = scan + 2 * W;                 // [L]
     double* cen0 = cen + L;                     // [L]
     uint32_t* fin = reinterpret_cast<uint32_t*>(cen0 + L);   // [L] smallest key of the cluster of rank i (none: kPadKey)
     int* misc = reinterpret_cast<int*>(fin + L);// [0], [1] selected index (by turns); [2] method flag; [40] as below
@@ -583,12 +631,7 @@ __global__ __launch_bounds__(T, 4) void quantize_sorted_kernel(
             double part = 0.0;
 #pragma unroll
             for (int e = 0; e < 16; ++e) part += mass[e];
-            double inc = part;
-#pragma unroll
-            for (int d = 1; d < 64; d <<= 1) {
-                const double o = shfl_up_f64(inc, d);
-                if (lane >= d) inc += o;
-            }
+            double inc = wave_inclusive_sum(part, lane);
             if (lane == 63) scan[(q & 1) * W + wv] = inc;          // (two sets of partial sums and of the selected
             if (tid == 0) misc[q & 1] = 0x7FFFFFFF;                // index, used by turns: one barrier less per centre)
             __syncthreads();
@@ -683,12 +726,7 @@ __global__ __launch_bounds__(T, 4) void quantize_sorted_kernel(
             cs += sw;
             csx += sw * x;
         }
-        double is = cs, isx = csx;
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const double o = shfl_up_f64(is, d), ox = shfl_up_f64(isx, d);
-            if (lane >= d) { is += o; isx += ox; }
-        }
+        double is = wave_inclusive_sum(cs, lane), isx = wave_inclusive_sum(csx, lane);
         if (lane == 63) { scan[2 * wv] = is; scan[2 * wv + 1] = isx; }
         __syncthreads();
         double bs = 0.0, bsx = 0.0;
@@ -720,11 +758,11 @@ __global__ __launch_bounds__(T, 4) void quantize_sorted_kernel(
         for (;;) {
             // order the centres by (value, index): rank r of centre q; sorted lane i takes the centre of rank i
             int r = 0;
-#pragma unroll
-            for (int p = 0; p < L; ++p) {
-                const double cp = shfl_f64(c, p);
+            static_for<L>([&](auto p_) {
+                constexpr int p = decltype(p_)::value;
+                const double cp = lane_f64<p>(c);
                 r += (cp < c || (cp == c && p < lane)) ? 1 : 0;
-            }
+            });
             const int to = (live ? r : lane) * 4;                  // the ranks are a permutation of the live lanes
             d = __hiloint2double(__builtin_amdgcn_ds_permute(to, __double2hiint(c)),
                                  __builtin_amdgcn_ds_permute(to, __double2loint(c)));
