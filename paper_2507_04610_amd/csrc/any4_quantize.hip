@@ -741,12 +741,13 @@ __global__ __launch_bounds__(T, 4) void quantize_sorted_kernel(
         if (tid == T - 1) { pre_s[T] = is; pre_sx[T] = isx; }
         __syncthreads();
     }
-
-    // ---- 3, sorted row: the Lloyd passes on the first 2^n lanes of wavefront 0.  Lane q holds centre q; after
-    // ordering, lane i also holds the centre of rank i: value d, index own, first position start, end.
+    // ---- 3, sorted row: the Lloyd passes on wavefront 0, four lanes per centre (lane = 4 q + sub: the four
+    // hold the same centre and split the searches and the partial sums).  Lanes 4 q .. 4 q + 3 hold centre q;
+    // after ordering, lanes 4 i .. 4 i + 3 also hold the centre of rank i: value d, index own, range [start, end).
     if (wv == 0) {
-        const bool live = lane < L;
-        double c = live ? cen[lane] : 0.0;
+        const int q4 = lane >> 2, sub = lane & 3, lane4 = lane & ~3;
+        const bool live = q4 < L;
+        double c = live ? cen[q4] : 0.0;
         const double maxabs = fmax(fabs((double)key_f32(kv[0].x)), fabs((double)key_f32(kv[pad16(K - 1)].x)));
         const double tol = centre_gap * maxabs;
         int prev_s = -2, prev_e = -2;                              // range of centre q in the previous pass
@@ -755,42 +756,46 @@ __global__ __launch_bounds__(T, 4) void quantize_sorted_kernel(
         double d = 0.0;
         int start = 0, end = 0;
         bool rep = false;
+        // sum over the four lanes of a centre: two DPP moves inside the group of four per half
+        auto quad_sum = [](double v) {
+            v += __hiloint2double(__builtin_amdgcn_update_dpp(0, __double2hiint(v), 0xB1, 0xF, 0xF, false),
+                                  __builtin_amdgcn_update_dpp(0, __double2loint(v), 0xB1, 0xF, 0xF, false));
+            v += __hiloint2double(__builtin_amdgcn_update_dpp(0, __double2hiint(v), 0x4E, 0xF, 0xF, false),
+                                  __builtin_amdgcn_update_dpp(0, __double2loint(v), 0x4E, 0xF, 0xF, false));
+            return v;
+        };
         for (;;) {
-            // order the centres by (value, index): rank r of centre q; sorted lane i takes the centre of rank i
+            // order the centres by (value, index): rank r of centre q; the lanes of rank i take that centre
             int r = 0;
             static_for<L>([&](auto p_) {
                 constexpr int p = decltype(p_)::value;
-                const double cp = lane_f64<p>(c);
-                r += (cp < c || (cp == c && p < lane)) ? 1 : 0;
+                const double cp = lane_f64<4 * p>(c);
+                r += (cp < c || (cp == c && p < q4)) ? 1 : 0;
             });
-            const int to = (live ? r : lane) * 4;                  // the ranks are a permutation of the live lanes
+            const int to = ((live ? r : q4) * 4 + sub) * 4;        // the ranks are a permutation of the live centres
             d = __hiloint2double(__builtin_amdgcn_ds_permute(to, __double2hiint(c)),
                                  __builtin_amdgcn_ds_permute(to, __double2loint(c)));
-            const int own = __builtin_amdgcn_ds_permute(to, lane);
+            const int own = __builtin_amdgcn_ds_permute(to, q4);
             // equal centres: only the lowest index ever wins a weight; it stands for the run
-            const double dprev = shfl_up_f64(d, 1);
-            rep = live && (lane == 0 || dprev != d);
-            const unsigned long long repmask = __ballot(rep);
-            const unsigned long long below = repmask & ((1ull << lane) - 1ull);
+            const double dprev = shfl_up_f64(d, 4);
+            rep = live && (q4 == 0 || dprev != d);
+            const unsigned long long repmask = __ballot(rep && sub == 0);
+            const unsigned long long below = repmask & ((1ull << lane4) - 1ull);
             const int prv = below ? 63 - __clzll(below) : 0;       // the previous run's first lane
             const int a_own = __shfl(own, prv);
-            bool bad = rep && lane > 0 && (d - dprev) <= tol;
-            // first sorted position at which a centre beats the one below it (the E-step's own comparison, which
-            // is false up to that position and true from it on).  Four lanes work for the centre of rank lane / 4:
-            // each round they probe the four inner fifths of the open range.
-            const int grp = lane >> 2, sub = lane & 3;
-            const double g_d = shfl_f64(d, grp), g_dprev = shfl_f64(dprev, grp);
-            const int g_own = __shfl(own, grp), g_aown = __shfl(a_own, grp);
-            const bool g_search = __shfl((rep && lane > 0) ? 1 : 0, grp) != 0;
-            int lo = 0, hi = g_search ? K : 0;                     // the answer lies in [lo, hi]
+            bool bad = rep && q4 > 0 && (d - dprev) <= tol;
+            // first sorted position at which this centre beats the one below it (the E-step's own comparison, which
+            // is false up to that position and true from it on): each round the four lanes probe the four
+            // inner fifths of the open range
+            int lo = 0, hi = (rep && q4 > 0) ? K : 0;              // the answer lies in [lo, hi]
             while (__ballot(lo < hi) != 0ull) {
                 const int span = hi - lo;
                 const int probe = lo + (span * (sub + 1)) / 5;     // lo <= probe < hi while the range is open
                 const double x = (double)key_f32(kv[pad16(min(probe, K - 1))].x);
-                const double da = x - g_dprev, db = x - g_d;
+                const double da = x - dprev, db = x - d;
                 const double dda = da * da, ddb = db * db;
-                const bool win = ddb < dda || (ddb == dda && g_own < g_aown);
-                const int losses = __popc((unsigned)(__ballot(!win) >> (grp * 4)) & 15u);   // 0 .. 4, the first ones
+                const bool win = ddb < dda || (ddb == dda && own < a_own);
+                const int losses = __popc((unsigned)(__ballot(!win) >> lane4) & 15u);   // 0 .. 4, the first ones
                 if (lo < hi) {
                     const int lo2 = losses > 0 ? lo + (span * losses) / 5 + 1 : lo;
                     const int hi2 = losses < 4 ? lo + (span * (losses + 1)) / 5 : hi;
@@ -798,29 +803,23 @@ __global__ __launch_bounds__(T, 4) void quantize_sorted_kernel(
                     hi = hi2;
                 }
             }
+            start = lo;
             // running sums before that position: the entry of its group of 16, then the group's first elements,
             // four apart per lane
-            double g_ss = 0.0, g_sx = 0.0;
+            double ss = 0.0, sx = 0.0;
             {
-                const int chunk = lo >> 4, nrem = lo & 15;
+                const int chunk = start >> 4, nrem = start & 15;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const int e = sub + 4 * i;
                     double x, sw;
                     element(min(chunk * 16 + e, K - 1), x, sw);
-                    if (e < nrem) { g_ss += sw; g_sx += sw * x; }
+                    if (e < nrem) { ss += sw; sx += sw * x; }
                 }
-                g_ss += shfl_xor_f64(g_ss, 1);
-                g_sx += shfl_xor_f64(g_sx, 1);
-                g_ss += shfl_xor_f64(g_ss, 2);
-                g_sx += shfl_xor_f64(g_sx, 2);
-                g_ss += pre_s[chunk];
-                g_sx += pre_sx[chunk];
+                ss = quad_sum(ss) + pre_s[chunk];
+                sx = quad_sum(sx) + pre_sx[chunk];
             }
-            const int from = min(lane, 15) * 4;                    // back to one lane per centre
-            start = __shfl(lo, from);
-            const double ss = shfl_f64(g_ss, from), sx = shfl_f64(g_sx, from);
-            const unsigned long long above = lane >= 63 ? 0ull : (repmask & ~((2ull << lane) - 1ull));
+            const unsigned long long above = lane4 >= 60 ? 0ull : (repmask & ~((1ull << (lane4 + 4)) - 1ull));
             const int nxt = above ? __ffsll((long long)above) - 1 : -1;
             const int s_nxt = __shfl(start, nxt < 0 ? 0 : nxt);
             end = nxt < 0 ? K : s_nxt;
@@ -833,22 +832,22 @@ __global__ __launch_bounds__(T, 4) void quantize_sorted_kernel(
             // did any weight change its centre?  compare every centre's range with the previous pass
             const bool some = rep && start < end;
             const int rs = some ? start : -1, re = some ? end : -1;
-            const int qs = __shfl(rs, r), qe = __shfl(re, r);
+            const int qs = __shfl(rs, r * 4), qe = __shfl(re, r * 4);
             const bool changed = __ballot(live && (qs != prev_s || qe != prev_e)) != 0ull;
             if (__ballot(bad) != 0ull) { fallback = true; break; }
             if ((done > 0 && !changed) || done >= iters) break;
             prev_s = qs;
             prev_e = qe;
-            c = shfl_f64(cn, r);
+            c = shfl_f64(cn, r * 4);
             ++done;
         }
         if (lane == 0) misc[2] = fallback ? 1 : 0;
         if (!fallback) {
-            // ---- 4. lane i holds the centre of rank i: table entry i, and code i for every weight from the
+            // ---- 4. lanes 4 i hold the centre of rank i: table entry i, and code i for every weight from the
             // first of its range up to the first of the next non-empty range
-            if (live) {
-                lut[n * L + lane] = (uint16_t)f32_to_bf16((float)d);
-                fin[lane] = (rep && start < end) ? kv[pad16(start)].x : kPadKey;
+            if (live && sub == 0) {
+                lut[n * L + q4] = (uint16_t)f32_to_bf16((float)d);
+                fin[q4] = (rep && start < end) ? kv[pad16(start)].x : kPadKey;
             }
             if (msteps && lane == 0) msteps[n] = done;
         }
