@@ -104,6 +104,23 @@ def test_noalloc_entry_point_checks_arguments_and_its_limit(lib):
     assert int(re.search(r"#define ANY4_NOALLOC_SCRATCH_BYTES \((\d+)u << 20\)", header).group(1)) << 20 == binding.NOALLOC_SCRATCH_BYTES
 
 
+def test_quantiser_entry_points_check_arguments(lib):
+    A = 0x1000
+    kmax = lib.any4_quantize_max_k()
+    assert kmax >= 14336 and kmax % 128 == 0
+    gap = lib.any4_quantize_with_gap
+    assert lib.any4_quantize(None, None, A, 1, 128, 4, 0, 1, A, A, A, A, None, None) == -1
+    assert lib.any4_quantize(A, None, A, 1, 128, 4, 0, 1, A, None, A, A, None, None) == -1
+    assert lib.any4_quantize(A, None, A, 1, 100, 4, 0, 1, A, A, A, A, None, None) == -2
+    assert lib.any4_quantize(A, None, A, 1, kmax + 128, 4, 0, 1, A, A, A, A, None, None) == -2
+    assert lib.any4_quantize(A, None, A, 1, 128, 4, 0, -1, A, A, A, A, None, None) == -2
+    assert lib.any4_quantize(A, None, A, 1, 128, 5, 0, 1, A, A, A, A, None, None) == -3
+    assert lib.any4_quantize(A, A + 4, A, 1, 128, 4, 0, 1, A, A, A, A, None, None) == -4
+    assert gap(A, None, A, 1, 128, 4, 0, 1, float("nan"), A, A, A, A, None, None) == -2
+    assert gap(None, None, A, 1, 128, 4, 0, 1, 0.0, A, A, A, A, None, None) == -1
+    assert gap(A, None, A, 1, 128, 4, 0, 1, -1.0, A + 8, A, A, A, None, None) == -4
+
+
 def test_repack_size(lib):
     # whole tiles of 16 rows; invalid arguments need nothing
     assert lib.any4_repack_bytes(16, 128, 4) == 16 * 64

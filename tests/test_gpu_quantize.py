@@ -119,6 +119,20 @@ def test_quantize_iteration_caps(any4, qoracle, iters):
     assert ref["msteps"].max() <= iters
 
 
+def test_quantize_many_rows_and_repeatability(any4, qoracle):
+    """More rows than the chip holds blocks at once (several rounds of blocks per compute unit), every row
+    against the oracle, and two runs of the same call bit-equal in everything they return."""
+    qc = inputs.make_quant_case(3000, 4096, 4, seed=99)
+    got, ref = run_and_compare(any4, qoracle, qc.w, qc.act, qc.u, 4, False, 20, "3000 rows")
+    again = any4.any4_quantize(torch.from_numpy(qc.w).cuda(), torch.from_numpy(qc.act).cuda(), torch.from_numpy(qc.u).cuda(),
+                               4, iters=20)
+    torch.cuda.synchronize()
+    for k in ("codes_u8", "msteps"):
+        assert torch.equal(got[k], again[k]), k
+    for k in ("lut", "scale", "offset"):
+        assert torch.equal(got[k].view(torch.int16), again[k].view(torch.int16)), k
+
+
 def test_quantize_long_rows(any4, qoracle):
     """The Llama-3 down projections' K, and the largest K the library accepts."""
     for K in (14336, any4.any4_quantize_max_k()):
