@@ -96,6 +96,8 @@ def test_quantize_methods_symmetric_caps_and_degenerate_rows(any4, qoracle, meth
     w[4, ::2] = -w[4, 1::2]                                 # pairs of equal magnitude: ties between centres
     act = qc.act.copy()
     act[::3] = 0.0
+    # no sampling mass at all: every centre is drawn by index and no centre ever moves
+    run_and_compare(any4, qoracle, qc.w, np.zeros_like(qc.act), qc.u, 4, False, 5, (method, "zero activations"), centre_gap=gap)
     for bits in (4, 3, 2):
         u = qc.u[:, :1 << bits].copy()
         # row 1 (constant) scales to exactly 0 without an offset-free scale; row 2 to four values that are no
