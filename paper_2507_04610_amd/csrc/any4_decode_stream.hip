@@ -113,7 +113,10 @@ struct Params {
     int lr;                          // log2(group size / 128): chunk g of 128 weights reads scale / offset g >> lr
                                      // of its row (rows of G >> lr entries)
     int slabs, slab_groups;          // groups per slab (the last slab may have fewer)
-    int blocks_per_slab, tiles;
+    int blocks_per_slab, tiles;      // grid = (blocks_per_slab, slabs)
+    int tpb, trem;                   // tiles / blocks_per_slab and the remainder: block b of a slab owns tpb tiles, the
+                                     // first trem blocks one more (computed by the host: two 64-bit divisions in the
+                                     // kernel are ~300 instructions in front of the first load)
     int one_table;                   // lut holds ONE row that serves every row of the matrix (built once per block)
 };
 
@@ -174,12 +177,11 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 15, q = lane >> 4;
 
-    const int slab = blockIdx.x / p.blocks_per_slab, bb = blockIdx.x - slab * p.blocks_per_slab;
-    if (slab >= p.slabs) return;
-    const int t0 = (int)((int64_t)bb * p.tiles / p.blocks_per_slab);
-    const int t1 = (int)((int64_t)(bb + 1) * p.tiles / p.blocks_per_slab);
-    if (t0 >= t1) return;
-    const int ntiles = t1 - t0;
+    const int slab = blockIdx.y, bb = blockIdx.x;
+    const int t0 = bb * p.tpb + min(bb, p.trem);
+    const int ntiles = p.tpb + (bb < p.trem ? 1 : 0);
+    const int t1 = t0 + ntiles;
+    if (ntiles <= 0) return;
 
     const int M = p.M, G = p.G;
     const int64_t N = p.N, K = p.K;
@@ -489,11 +491,16 @@ __global__ __launch_bounds__(kWaves * 64, 1) void decode_stream_kernel(const Par
     uint4 xa[GW][4];
     uint4 xraw[kTile];
     if (compact) {
+        // through a buffer descriptor over the M rows: a lane without a piece takes an offset beyond the
+        // range and gets zeros without a memory access, so the load is unconditional.  (A load under a
+        // per-lane condition is followed by a wait for ALL outstanding loads: here that wait stood in
+        // front of the first code load, a whole trip to memory before the stream even started.)
+        const __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.x), 0, (int)(M * K * 2), 0x00020000);
 #pragma unroll
         for (int m = 0; m < 2; ++m) {
-            xraw[m] = make_uint4(0, 0, 0, 0);
-            if (m < M && has)
-                xraw[m] = *reinterpret_cast<const uint4*>(p.x + (int64_t)m * K + (int64_t)gw0 * kGroup + lane * 8);
+            const uint32_t vo = (m < M && has) ? (uint32_t)((m * K + (int64_t)gw0 * kGroup + lane * 8) * 2) : 0x80000000u;
+            const auto v = __builtin_amdgcn_raw_buffer_load_b128(xr, vo, 0, 0);
+            xraw[m] = make_uint4(v[0], v[1], v[2], v[3]);
         }
     } else {
         const uint16_t* xsrc = p.x + (int64_t)gw0 * kGroup + (has ? lane : 0) * 8;
@@ -903,7 +910,8 @@ static hipError_t launch_stream_t(const Params& p, int grid, hipStream_t stream)
     constexpr auto kern = stream::decode_stream_kernel<BITS, GW, AUX, NOLUT, REPACK, COARSE, FINE, F16>;
     constexpr int lds = stream::lds_bytes(BITS, FINE && AUX);
     if (hipError_t e = ensure_lds<kern>(lds); e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(stream::kWaves * 64), lds, stream, p);
+    if (grid != p.blocks_per_slab * p.slabs) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(kern, dim3((unsigned)p.blocks_per_slab, (unsigned)p.slabs), dim3(stream::kWaves * 64), lds, stream, p);
     return hipGetLastError();
 }
 
@@ -933,6 +941,8 @@ hipError_t launch_decode_stream(const uint16_t* x, const uint32_t* codes, const 
     p.N = N; p.K = K; p.M = (int)M; p.G = (int)(K / kGroup); p.lr = lr;
     p.slabs = sp.slabs; p.slab_groups = sp.slab_groups; p.blocks_per_slab = sp.blocks_per_slab;
     p.tiles = (int)sp.tiles;
+    p.tpb = p.tiles / sp.blocks_per_slab;
+    p.trem = p.tiles % sp.blocks_per_slab;
     p.one_table = one_table ? 1 : 0;
     const int grid = sp.slabs * sp.blocks_per_slab;
     if (f16) {
