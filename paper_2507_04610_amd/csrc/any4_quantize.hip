@@ -755,7 +755,8 @@ __global__ __launch_bounds__(T, 4) void quantize_sorted_kernel(
         bool fallback = false;
         double d = 0.0;
         int start = 0, end = 0;
-        bool rep = false;
+        bool rep = false, ranked = false;
+        int r = 0;
         // sum over the four lanes of a centre: two DPP moves inside the group of four per half
         auto quad_sum = [](double v) {
             v += __hiloint2double(__builtin_amdgcn_update_dpp(0, __double2hiint(v), 0xB1, 0xF, 0xF, false),
@@ -765,17 +766,31 @@ __global__ __launch_bounds__(T, 4) void quantize_sorted_kernel(
             return v;
         };
         for (;;) {
-            // order the centres by (value, index): rank r of centre q; the lanes of rank i take that centre
-            int r = 0;
-            static_for<L>([&](auto p_) {
-                constexpr int p = decltype(p_)::value;
-                const double cp = lane_f64<4 * p>(c);
-                r += (cp < c || (cp == c && p < q4)) ? 1 : 0;
-            });
-            const int to = ((live ? r : q4) * 4 + sub) * 4;        // the ranks are a permutation of the live centres
-            d = __hiloint2double(__builtin_amdgcn_ds_permute(to, __double2hiint(c)),
-                                 __builtin_amdgcn_ds_permute(to, __double2loint(c)));
-            const int own = __builtin_amdgcn_ds_permute(to, q4);
+            // order the centres by (value, index): rank r of centre q; the lanes of rank i take that centre.
+            // The order of the last pass is tried first (one permutation and a comparison of neighbours; the
+            // centres of a one-dimensional k-means hardly ever overtake each other) and the ranks counted anew,
+            // 2^n comparisons per centre, only if it no longer holds.
+            int own = 0;
+            for (int attempt = ranked ? 0 : 1; attempt < 2; ++attempt) {
+                if (attempt == 1) {
+                    r = 0;
+                    static_for<L>([&](auto p_) {
+                        constexpr int p = decltype(p_)::value;
+                        const double cp = lane_f64<4 * p>(c);
+                        r += (cp < c || (cp == c && p < q4)) ? 1 : 0;
+                    });
+                }
+                const int to = ((live ? r : q4) * 4 + sub) * 4;    // the ranks are a permutation of the live centres
+                d = __hiloint2double(__builtin_amdgcn_ds_permute(to, __double2hiint(c)),
+                                     __builtin_amdgcn_ds_permute(to, __double2loint(c)));
+                own = __builtin_amdgcn_ds_permute(to, q4);
+                if (attempt == 1) break;
+                const double below_d = shfl_up_f64(d, 4);
+                const int below_own = __shfl_up(own, 4);
+                const bool in_order = !live || q4 == 0 || below_d < d || (below_d == d && below_own < own);
+                if (__ballot(!in_order) == 0ull) break;
+            }
+            ranked = true;
             // equal centres: only the lowest index ever wins a weight; it stands for the run
             const double dprev = shfl_up_f64(d, 4);
             rep = live && (q4 == 0 || dprev != d);
